@@ -112,7 +112,7 @@ int orc_get_layout(uint64_t n, const orc_fmt* fmt, uint32_t align, orc_layout* L
         L->off_spike_idx = off;
         off += L->n_groups * 2;
     }
-    L->total_bytes = off;
+    L->total_bytes = round_up(off, align);  // records follow each other at aligned addresses
     return ORC_OK;
 }
 

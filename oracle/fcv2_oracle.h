@@ -51,7 +51,8 @@ typedef struct {
     uint64_t off_scale, off_zero, off_spike_val, off_spike_idx;
 } orc_layout;
 
-/* Section offsets of one packed record of n elements; every section starts at a multiple of align. */
+/* Section offsets of one packed record of n elements; every section starts at a multiple of align and
+ * total_bytes is rounded up to it. */
 int orc_get_layout(uint64_t n, const orc_fmt* fmt, uint32_t align, orc_layout* out);
 
 /* Order key of a bf16 bit pattern (total order, -0 < +0). */

@@ -1,0 +1,133 @@
+// fcv2_bits.h -- integer building blocks of the codec kernels: bf16 bit handling, order keys, and the
+// shift/mask sequences that move code fields between "one code per byte" registers and the packed bit planes
+// (Section 3.2 of arxiv 2508.03760: a b-bit code is split into 4/2/1-bit planes stored separately).
+//
+// Everything here is plain 32-bit integer arithmetic, usable from host and device, so the sequences can be
+// unit-tested on the CPU.  A lane of the kernels always works on 8 consecutive elements:
+//   c0 = codes of elements 0..3, one per byte (element 0 in bits 0..7), c1 = elements 4..7.
+#pragma once
+#include <math.h>
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define FCV2_HD __host__ __device__ __forceinline__
+#else
+#define FCV2_HD inline
+#endif
+
+// Keeps the compiler from merging a chain of shift-or steps into one 32-bit multiply (quarter rate on CDNA).
+#if defined(__HIP_DEVICE_COMPILE__)
+#define FCV2_KEEP(v) asm volatile("" : "+v"(v))
+#else
+#define FCV2_KEEP(v) (void)(v)
+#endif
+
+namespace fcv2 {
+
+// ---- plane structure of a b-bit code: widest plane first = most significant bits ---------------------------
+template <int BITS> struct Planes;
+template <> struct Planes<2> { static constexpr int w8 = 0, w4 = 0, w2 = 1, w1 = 0, sh4 = 0, sh2 = 0, sh1 = 0; };
+template <> struct Planes<3> { static constexpr int w8 = 0, w4 = 0, w2 = 1, w1 = 1, sh4 = 0, sh2 = 1, sh1 = 0; };
+template <> struct Planes<4> { static constexpr int w8 = 0, w4 = 1, w2 = 0, w1 = 0, sh4 = 0, sh2 = 0, sh1 = 0; };
+template <> struct Planes<5> { static constexpr int w8 = 0, w4 = 1, w2 = 0, w1 = 1, sh4 = 1, sh2 = 0, sh1 = 0; };
+template <> struct Planes<6> { static constexpr int w8 = 0, w4 = 1, w2 = 1, w1 = 0, sh4 = 2, sh2 = 0, sh1 = 0; };
+template <> struct Planes<7> { static constexpr int w8 = 0, w4 = 1, w2 = 1, w1 = 1, sh4 = 3, sh2 = 1, sh1 = 0; };
+template <> struct Planes<8> { static constexpr int w8 = 1, w4 = 0, w2 = 0, w1 = 0, sh4 = 0, sh2 = 0, sh1 = 0; };
+
+// ---- bf16 ---------------------------------------------------------------------------------------------------
+// Total order on bf16 bit patterns that equals numeric order on finite values, with -0 below +0.
+FCV2_HD uint32_t key_of_bf16(uint32_t u) { return (u & 0x8000u) ? (~u & 0xFFFFu) : (u | 0x8000u); }
+FCV2_HD uint32_t bf16_of_key(uint32_t k) { return (k & 0x8000u) ? (k ^ 0x8000u) : (~k & 0xFFFFu); }
+
+// fp32 bits -> bf16 bits, round to nearest even; NaN stays a quiet NaN.
+FCV2_HD uint32_t bf16_rne_bits(uint32_t u) {
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;
+    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Smallest bf16-representable fp32 bit pattern that is >= the (positive, finite) input.
+FCV2_HD uint32_t bf16_round_up_bits(uint32_t u) { return (u + 0xFFFFu) & 0xFFFF0000u; }
+
+// d / QMAX with IEEE rounding for d >= 0, without the long division sequence: multiply by the rounded
+// reciprocal, then one exact-residual correction (Markstein).  Checked against IEEE division for every fp32
+// significand and every QMAX = 2^b - 1 by the host tests; +inf and NaN are passed through.
+template <int QMAX> FCV2_HD float div_by_qmax(float d) {
+    constexpr float y = 1.0f / (float)QMAX;
+    const float q0 = d * y;
+    const float r = fmaf(-(float)QMAX, q0, d);
+    const float q1 = fmaf(r, y, q0);
+    return (d < INFINITY) ? q1 : d;
+}
+
+// ---- codes (one per byte) -> planes ---------------------------------------------------------------------------
+// Field (code >> SH) & (2^W - 1) of each byte, moved to the top W bits of that byte.
+template <int W, int SH, int BITS> FCV2_HD uint32_t top_align(uint32_t c) {
+    constexpr int lsh = 8 - W - SH;
+    constexpr uint32_t m = (((0xFFu << (8 - W)) & 0xFFu) * 0x01010101u);
+    uint32_t f = lsh > 0 ? (c << (lsh > 0 ? lsh : 0)) : c;
+    // when the field reaches up to the top bit of the code nothing can spill into the next byte
+    return (SH + W == BITS && SH == 0) ? f : (f & m);
+}
+
+// 8 nibbles: bits 4i..4i+3 = field of element i.
+template <int SH, int BITS> FCV2_HD uint32_t pack_plane4(uint32_t c0, uint32_t c1) {
+    uint32_t f0 = top_align<4, SH, BITS>(c0), f1 = top_align<4, SH, BITS>(c1);
+    uint32_t a0 = (f0 << 4) | f0;  // bytes 1 and 3 hold (e0 | e1 << 4) and (e2 | e3 << 4)
+    uint32_t a1 = (f1 << 4) | f1;
+    return ((a0 >> 8) & 0xFFu) | ((a0 >> 16) & 0xFF00u) | ((a1 << 8) & 0xFF0000u) | (a1 & 0xFF000000u);
+}
+
+// 8 two-bit fields: bits 2i..2i+1 = field of element i (16 bits).
+template <int SH, int BITS> FCV2_HD uint32_t pack_plane2(uint32_t c0, uint32_t c1) {
+    uint32_t f0 = top_align<2, SH, BITS>(c0), f1 = top_align<2, SH, BITS>(c1);
+    uint32_t a0 = (f0 << 6) | f0, a1 = (f1 << 6) | f1;
+    FCV2_KEEP(a0);
+    FCV2_KEEP(a1);
+    uint32_t b0 = (a0 << 12) | a0, b1 = (a1 << 12) | a1;  // top byte = e0 | e1<<2 | e2<<4 | e3<<6
+    return (b0 >> 24) | ((b1 >> 16) & 0xFF00u);
+}
+
+// 8 one-bit fields: bit i = field of element i (8 bits).
+template <int SH, int BITS> FCV2_HD uint32_t pack_plane1(uint32_t c0, uint32_t c1) {
+    uint32_t f0 = top_align<1, SH, BITS>(c0), f1 = top_align<1, SH, BITS>(c1);  // bit 7 of every byte
+    uint32_t m = (f0 >> 4) | f1;                                                 // e_i at 8i+3, e_{i+4} at 8i+7
+    uint32_t a = (m << 7) | m;
+    FCV2_KEEP(a);
+    uint32_t b = (a << 14) | a;
+    return b >> 24;
+}
+
+// ---- planes -> codes --------------------------------------------------------------------------------------------
+// 8 one-bit fields (bit i) -> 8 nibbles (bit 4i).
+FCV2_HD uint32_t spread1to4(uint32_t x) {
+    x = (x | (x << 12)) & 0x000F000Fu;
+    x = (x | (x << 6)) & 0x03030303u;
+    x = (x | (x << 3)) & 0x11111111u;
+    return x;
+}
+// 8 two-bit fields (bits 2i) -> 8 nibbles (bits 4i).
+FCV2_HD uint32_t spread2to4(uint32_t x) {
+    x = (x | (x << 8)) & 0x00FF00FFu;
+    x = (x | (x << 4)) & 0x0F0F0F0Fu;
+    x = (x | (x << 2)) & 0x33333333u;
+    return x;
+}
+
+// Codes of the 8 elements as two "even/odd" registers: ev = elements 0,2,4,6 one per byte, od = 1,3,5,7.
+// p4 / p2 / p1 are the lane's 32 / 16 / 8 bits of the planes; for BITS == 8 use the plane bytes directly.
+template <int BITS> FCV2_HD void codes_even_odd(uint32_t p4, uint32_t p2, uint32_t p1, uint32_t& ev, uint32_t& od) {
+    using P = Planes<BITS>;
+    constexpr uint32_t M = 0x0F0F0F0Fu;
+    uint32_t low = 0;  // nibble word of the planes below the 4-bit plane
+    if (P::w2) low = spread2to4(p2) << P::sh2;
+    if (P::w1) low |= spread1to4(p1);
+    if (P::w4) {
+        ev = ((p4 & M) << P::sh4) | (low & M);
+        od = (((p4 >> 4) & M) << P::sh4) | ((low >> 4) & M);
+    } else {
+        ev = low & M;
+        od = (low >> 4) & M;
+    }
+}
+
+}  // namespace fcv2

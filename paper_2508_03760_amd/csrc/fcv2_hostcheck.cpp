@@ -1,0 +1,78 @@
+// fcv2_hostcheck.cpp -- host build of the kernels' integer/float building blocks (fcv2_bits.h) behind a C
+// interface, so that the CPU test suite can exercise exactly the sequences the kernels run.
+// Build: g++ -std=c++17 -O2 -ffp-contract=off -fPIC -shared.
+#include <cstring>
+
+#include "fcv2_bits.h"
+
+using namespace fcv2;
+
+template <int BITS> static void planes_of_codes(const uint8_t* codes, uint32_t* p8lo, uint32_t* p8hi, uint32_t* p4, uint32_t* p2,
+                                                uint32_t* p1) {
+    uint32_t c0, c1;
+    std::memcpy(&c0, codes, 4);
+    std::memcpy(&c1, codes + 4, 4);
+    using P = Planes<BITS>;
+    *p8lo = c0;
+    *p8hi = c1;
+    *p4 = P::w4 ? pack_plane4<P::sh4, BITS>(c0, c1) : 0;
+    *p2 = P::w2 ? pack_plane2<P::sh2, BITS>(c0, c1) & 0xFFFFu : 0;
+    *p1 = P::w1 ? pack_plane1<P::sh1, BITS>(c0, c1) & 0xFFu : 0;
+}
+
+template <int BITS> static void codes_of_planes(uint32_t p4, uint32_t p2, uint32_t p1, uint8_t* codes) {
+    uint32_t ev, od;
+    codes_even_odd<BITS>(p4, p2, p1, ev, od);
+    for (int i = 0; i < 4; ++i) {
+        codes[2 * i] = (uint8_t)(ev >> (8 * i));
+        codes[2 * i + 1] = (uint8_t)(od >> (8 * i));
+    }
+}
+
+template <int QMAX> static uint64_t div_mismatches(uint32_t first_bits, uint32_t count) {
+    uint64_t bad = 0;
+    for (uint32_t i = 0; i < count; ++i) {
+        uint32_t u = first_bits + i;
+        float d;
+        std::memcpy(&d, &u, 4);
+        float a = div_by_qmax<QMAX>(d), b = d / (float)QMAX;
+        if (std::memcmp(&a, &b, 4) != 0 && !(a != a && b != b)) ++bad;
+    }
+    return bad;
+}
+
+extern "C" {
+
+int hc_planes_of_codes(int bits, const uint8_t* codes, uint32_t* out5) {
+    switch (bits) {
+#define C(B) case B: planes_of_codes<B>(codes, out5, out5 + 1, out5 + 2, out5 + 3, out5 + 4); return 0;
+        C(2) C(3) C(4) C(5) C(6) C(7) C(8)
+#undef C
+    }
+    return -1;
+}
+
+int hc_codes_of_planes(int bits, uint32_t p4, uint32_t p2, uint32_t p1, uint8_t* codes) {
+    switch (bits) {
+#define C(B) case B: codes_of_planes<B>(p4, p2, p1, codes); return 0;
+        C(2) C(3) C(4) C(5) C(6) C(7)
+#undef C
+    }
+    return -1;
+}
+
+// Number of fp32 bit patterns in [first_bits, first_bits + count) where the short division differs from d / qmax.
+uint64_t hc_div_mismatches(int qmax, uint32_t first_bits, uint32_t count) {
+    switch (qmax) {
+#define C(Q) case Q: return div_mismatches<Q>(first_bits, count);
+        C(3) C(7) C(15) C(31) C(63) C(127) C(255)
+#undef C
+    }
+    return ~0ull;
+}
+
+uint32_t hc_key_of_bf16(uint32_t u) { return key_of_bf16(u); }
+uint32_t hc_bf16_of_key(uint32_t k) { return bf16_of_key(k); }
+uint32_t hc_bf16_rne_bits(uint32_t u) { return bf16_rne_bits(u); }
+uint32_t hc_bf16_round_up_bits(uint32_t u) { return bf16_round_up_bits(u); }
+}

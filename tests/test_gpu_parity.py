@@ -1,0 +1,283 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element, on the same
+seeded inputs.  Packed planes, metadata, spike values/indices, offsets and row maps must be bit-identical;
+fp32 outputs must agree within 1e-3 absolute + 1e-3 relative (they are expected to be identical too).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle as O
+from paper_2508_03760_amd import fcv2
+from paper_2508_03760_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+SR, F32 = fcv2.F_SPIKE, fcv2.F_META_FP32
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    fcv2.lib()  # fails loudly if the HIP library is missing
+    yield
+    torch.cuda.synchronize()
+
+
+def to_dev_bf16(bits_u16):
+    return torch.from_numpy(np.ascontiguousarray(bits_u16).view(np.int16)).to(DEV).view(torch.bfloat16)
+
+
+def sections(L, flags):
+    m = 4 if flags & F32 else 2
+    out = []
+    for w in (8, 4, 2, 1):
+        off = getattr(L, f"off_plane{w}")
+        if off != O.ABSENT:
+            out.append((f"plane{w}", off, L.n * w // 8))
+    out += [("scale", L.off_scale, m * L.n_groups), ("zero", L.off_zero, m * L.n_groups)]
+    if flags & SR:
+        out += [("spike_val", L.off_spike_val, 4 * L.n_groups), ("spike_idx", L.off_spike_idx, 2 * L.n_groups)]
+    return out
+
+
+def assert_packed_equal(got, want, L, flags, what=""):
+    got = np.asarray(got).reshape(-1)
+    want = np.asarray(want).reshape(-1)
+    for name, off, size in sections(L, flags):
+        a, b = got[off:off + size], want[off:off + size]
+        if not np.array_equal(a, b):
+            bad = np.nonzero(a != b)[0]
+            raise AssertionError(f"{what}: section {name} differs at {bad.size} of {size} bytes, first at {bad[0]}: "
+                                 f"gpu {a[bad[0]]} oracle {b[bad[0]]}")
+
+
+def assert_close(got, want, what=""):
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    bad = np.abs(got - want) > 1e-3 + 1e-3 * np.abs(want)
+    assert not bad.any(), f"{what}: {bad.sum()} values outside 1e-3 abs + 1e-3 rel, first at {np.nonzero(bad)[0][0]}"
+
+
+def check_codec(x_u16, bits, group, flags, what):
+    """quantize_pack + both unpack_dequant outputs against the oracle; returns the GPU packed record."""
+    x_u16 = np.ascontiguousarray(x_u16).reshape(-1)
+    n = x_u16.size
+    L = O.get_layout(n, bits, group, flags)
+    want = O.quantize_pack(x_u16, bits, group, flags)
+    got = fcv2.quantize_pack(to_dev_bf16(x_u16), bits, group, flags)
+    assert got.numel() == L.total_bytes
+    assert_packed_equal(got.cpu().numpy(), want, L, flags, f"quantize_pack {what}")
+    v = fcv2.unpack_dequant(got, n, bits, group, flags, torch.float32).cpu().numpy()
+    vo = O.unpack_dequant(want, n, bits, group, flags, O.DT_FP32)
+    assert_close(v, vo, f"unpack_dequant fp32 {what}")
+    assert np.array_equal(v.view(np.uint32), vo.view(np.uint32)), f"unpack_dequant fp32 {what}: not bit-identical"
+    vb = fcv2.unpack_dequant(got, n, bits, group, flags, torch.bfloat16).view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(vb, O.unpack_dequant(want, n, bits, group, flags, O.DT_BF16)), f"unpack_dequant bf16 {what}"
+    return got
+
+
+# ---- small shapes: several tiles and a ragged tail, every format -----------------------------------------------
+
+@pytest.mark.parametrize("bits", range(2, 9))
+@pytest.mark.parametrize("group", [32, 64, 128, 256])
+def test_codec_all_formats(bits, group):
+    n = 2048 * 3 + 3 * 256  # three full 256-lane blocks plus a partial one
+    x = W.tensor(2, 0, rows=1, cols=n).reshape(-1)
+    for flags in (SR, 0, SR | F32, F32):
+        check_codec(x, bits, group, flags, f"b{bits} g{group} f{flags}")
+
+
+@pytest.mark.parametrize("bits", [2, 3, 5, 8])
+def test_codec_single_group_and_tiny_inputs(bits):
+    for group in (32, 64, 128, 256):
+        for ngroups in (1, 2, 7):
+            x = W.tensor(4, 1, rows=1, cols=group * ngroups).reshape(-1)
+            check_codec(x, bits, group, SR, f"tiny b{bits} g{group} x{ngroups}")
+
+
+def _edge_groups(group):
+    rng = np.random.default_rng(group)
+    rows = []
+    rows.append(np.full(group, 1.25))                                   # constant group
+    rows.append(np.zeros(group))                                        # all +0
+    r = np.zeros(group); r[::2] = -0.0; rows.append(r)                  # -0 / +0 mix (ties in value, not in key)
+    rows.append(rng.integers(-2, 3, group) * 0.5)                       # many ties
+    r = np.full(group, 3.0); r[5] = -7.0; rows.append(r)                # everything but the minimum equal
+    r = np.full(group, -3.0); r[group - 1] = 9.0; rows.append(r)        # everything but the maximum equal
+    r = np.full(group, 2.0); r[3] = 2.0; r[9] = 100.0; r[17] = -100.0; rows.append(r)
+    r = rng.standard_normal(group); r[0] = 1e30; r[1] = -1e30; rows.append(r)       # spikes far outside
+    rows.append(rng.standard_normal(group) * 1e-30)                     # tiny magnitudes
+    rows.append(rng.standard_normal(group) * 1e-42)                     # range below the 2^-64 threshold
+    rows.append(rng.standard_normal(group) * 3e37)                      # near the top of the range
+    rows.append(np.linspace(-1, 1, group))                              # exact halves appear at some widths
+    rows.append(np.arange(group, dtype=np.float64))                     # integers: ties to even at .5
+    r = np.abs(rng.standard_normal(group)) + 4; rows.append(r)          # all positive
+    r = -np.abs(rng.standard_normal(group)) - 4; rows.append(r)         # all negative
+    for pos in (0, 7, 8, group - 1):                                    # spikes on lane borders
+        r = rng.standard_normal(group); r[pos] = 50.0; r[(pos + 8) % group] = -50.0; rows.append(r)
+    return W.f32_to_bf16_bits(np.concatenate(rows).astype(np.float32))
+
+
+@pytest.mark.parametrize("bits", range(2, 9))
+@pytest.mark.parametrize("group", [32, 64, 128, 256])
+def test_codec_edge_cases(bits, group):
+    x = _edge_groups(group)
+    for flags in (SR, 0, SR | F32):
+        check_codec(x, bits, group, flags, f"edge b{bits} g{group} f{flags}")
+
+
+def test_range_overflow_is_deterministic():
+    """hi - lo = +inf (inputs beyond 2^127 apart): outside the contract of finite ranges, but the packed record
+    still matches the oracle (infinite scale, all codes 0) and decoding yields NaN at the same positions."""
+    rng = np.random.default_rng(3)
+    x = W.f32_to_bf16_bits(np.clip(rng.standard_normal(1024) * 3e38, -3.3e38, 3.3e38).astype(np.float32))
+    for bits in (2, 5, 8):
+        L = O.get_layout(x.size, bits, 128, SR)
+        want = O.quantize_pack(x, bits, 128, SR)
+        got = fcv2.quantize_pack(to_dev_bf16(x), bits, 128, SR)
+        assert_packed_equal(got.cpu().numpy(), want, L, SR, f"overflow b{bits}")
+        v = fcv2.unpack_dequant(got, x.size, bits, 128, SR).cpu().numpy()
+        vo = O.unpack_dequant(want, x.size, bits, 128, SR)
+        assert np.array_equal(np.isnan(v), np.isnan(vo))
+        assert np.array_equal(v[~np.isnan(v)], vo[~np.isnan(vo)])
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_every_scale_value(bits):
+    """Groups [0, hi, hi/2, ...] for every positive finite bf16 hi: sweeps every scale significand and exponent
+    the encoder's reciprocal can meet."""
+    hi = np.arange(0x0080, 0x7F80, dtype=np.uint16)  # all positive normal bf16 values
+    hf = W.bf16_bits_to_f32(hi).astype(np.float64)
+    frac = np.concatenate([[0.0, 1.0], np.linspace(0.02, 0.98, 30)])
+    x = W.f32_to_bf16_bits((hf[:, None] * frac[None, :]).astype(np.float32)).reshape(-1)
+    check_codec(x, bits, 32, 0, f"scales b{bits}")
+    check_codec(x, bits, 32, SR, f"scales sr b{bits}")
+
+
+# ---- reduce_requant -----------------------------------------------------------------------------------------------
+
+def check_reduce(xs, bits, group, flags, what, flags_out=None):
+    n = xs[0].size
+    fin = (bits, group, flags)
+    fout = (bits, group, flags if flags_out is None else flags_out)
+    peers_o = [O.quantize_pack(x, *fin) for x in xs]
+    peers_g = [torch.from_numpy(p).to(DEV) for p in peers_o]
+    want, s_want = O.reduce_requant(peers_o, n, fin, fout, want_sum=True)
+    got, s_got = fcv2.reduce_requant(peers_g, n, fin, fout, want_sum=True)
+    assert_close(s_got.cpu().numpy(), s_want, f"reduce sum {what}")
+    assert np.array_equal(s_got.cpu().numpy().view(np.uint32), s_want.view(np.uint32)), f"reduce sum {what}: bits differ"
+    Lout = O.get_layout(n, *fout)
+    assert_packed_equal(got.cpu().numpy(), want, Lout, fout[2], f"reduce_requant {what}")
+    got2 = fcv2.reduce_requant(peers_g, n, fin, fout)  # without the optional sum output
+    assert_packed_equal(got2.cpu().numpy(), want, Lout, fout[2], f"reduce_requant (no sum) {what}")
+
+
+@pytest.mark.parametrize("bits", range(2, 9))
+@pytest.mark.parametrize("group", [32, 64, 128, 256])
+def test_reduce_requant_all_formats(bits, group):
+    n = 2048 * 2 + 512
+    xs = [W.tensor(2, p, rows=1, cols=n).reshape(-1) for p in range(8)]
+    check_reduce(xs, bits, group, SR, f"b{bits} g{group} N8")
+    check_reduce(xs[:3], bits, group, 0, f"b{bits} g{group} N3 no-sr")
+
+
+@pytest.mark.parametrize("n_peers", [1, 2, 5, 16])
+def test_reduce_requant_peer_counts(n_peers):
+    n = 4096 + 256
+    xs = [W.tensor(4, p, rows=1, cols=n).reshape(-1) for p in range(n_peers)]
+    check_reduce(xs, 3, 128, SR, f"N{n_peers}")
+    check_reduce(xs, 6, 64, SR | F32, f"N{n_peers} fp32 meta", flags_out=SR)
+
+
+def test_reduce_requant_edge_cases():
+    for group in (32, 128, 256):
+        base = _edge_groups(group)
+        xs = [base, base[::-1].copy(), np.roll(base, group)]
+        check_reduce(xs, 4, group, SR, f"edge g{group}")
+        check_reduce(xs, 2, group, SR, f"edge g{group} b2")
+
+
+# ---- dispatch_quant -------------------------------------------------------------------------------------------------
+
+def check_dispatch(x, ids, E, bits, group, flags, what):
+    T, H = x.shape
+    send_o, offs_o, src_o = O.dispatch_quant(x, ids, E, bits, group, flags)
+    send, offs, src = fcv2.dispatch_quant(to_dev_bf16(x).view(T, H), torch.from_numpy(ids).to(DEV), E, bits, group, flags)
+    R = int(offs_o[E])
+    assert np.array_equal(offs.cpu().numpy(), offs_o), f"{what}: expert_offsets"
+    assert np.array_equal(src.cpu().numpy()[:R], src_o), f"{what}: row_src"
+    L = O.get_layout(H, bits, group, flags, 16)
+    got = send.cpu().numpy()[:R]
+    for name, off, size in sections(L, flags):
+        assert np.array_equal(got[:, off:off + size], send_o[:, off:off + size]), f"{what}: rows differ in {name}"
+
+
+@pytest.mark.parametrize("bits,group,flags", [(2, 128, SR), (3, 32, SR), (4, 64, 0), (5, 128, SR | F32), (7, 256, SR), (8, 128, SR)])
+def test_dispatch_quant_small(bits, group, flags):
+    T, H, K, E = 300, 768, 4, 40  # slots not a multiple of the planning chunk, rows not a multiple of a block
+    x = W.tensor(3, 0, rows=T, cols=H)
+    ids = W.topk_routing(W.seed_for(3), T, E, K)
+    ids[5, 2] = -1
+    ids[9, :] = -1
+    ids[T - 1, 0] = -1
+    check_dispatch(x, ids, E, bits, group, flags, f"dispatch b{bits} g{group}")
+
+
+def test_dispatch_quant_degenerate_routing():
+    T, H, K, E = 130, 512, 8, 256
+    x = W.tensor(3, 1, rows=T, cols=H)
+    one = np.full((T, K), 7, np.int32)  # every copy to one expert: longest possible stable run
+    check_dispatch(x, one, E, 2, 128, SR, "all to one expert")
+    none = np.full((T, K), -1, np.int32)  # nothing routed
+    send, offs, src = fcv2.dispatch_quant(to_dev_bf16(x).view(T, H), torch.from_numpy(none).to(DEV), E, 2, 128, SR)
+    assert int(offs.cpu().numpy().max()) == 0
+
+
+# ---- the five workloads at full size, in the launch configuration the benchmark times ----------------------------------
+
+def test_workload1_full():
+    x = W.tensor(1, 0).reshape(-1)
+    check_codec(x, 4, 128, SR, "workload 1")
+    xs = [W.tensor(1, p).reshape(-1) for p in range(4)]
+    check_reduce(xs, 4, 128, SR, "workload 1 N4")
+
+
+@pytest.mark.parametrize("bits", [3, 2, 4, 5, 6, 7, 8])
+def test_workload2_full(bits):
+    xs = [W.tensor(2, p).reshape(-1) for p in range(8)]
+    check_codec(xs[0], bits, 128, SR, f"workload 2 b{bits}")
+    check_reduce(xs, bits, 128, SR, f"workload 2 b{bits} N8")
+
+
+def test_workload3_full():
+    w = W.WORKLOADS[3]
+    x = W.tensor(3, 0)
+    ids = W.topk_routing(W.seed_for(3), w["rows"], w["experts"], w["topk"])
+    check_dispatch(x, ids, w["experts"], 2, 128, SR, "workload 3")
+
+
+@pytest.mark.parametrize("bits,group", [(5, 64), (6, 256)])
+def test_workload4_full(bits, group):
+    xs = [W.tensor(4, p).reshape(-1) for p in range(8)]
+    check_codec(xs[0], bits, group, SR, f"workload 4 b{bits} g{group}")
+    check_reduce(xs, bits, group, SR, f"workload 4 b{bits} g{group} N8")
+
+
+@pytest.mark.parametrize("bits,group", [(5, 256), (6, 64)])
+def test_workload4_other_formats_sampled(bits, group):
+    # the other two format pairs of workload 4, on a 1/16 slice of the rows
+    xs = [W.tensor(4, p, rows=512).reshape(-1) for p in range(8)]
+    check_codec(xs[0], bits, group, SR, f"workload 4 slice b{bits} g{group}")
+    check_reduce(xs, bits, group, SR, f"workload 4 slice b{bits} g{group} N8")
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_workload5_full(bits):
+    xs = [W.tensor(5, p).reshape(-1) for p in range(8)]
+    g = check_codec(xs[0], bits, 128, SR, f"workload 5 b{bits}")
+    # back-to-back calls on one stream give the same record every time
+    xd = to_dev_bf16(xs[0])
+    outs = [fcv2.quantize_pack(xd, bits, 128, SR) for _ in range(50)]
+    torch.cuda.synchronize()
+    assert all(torch.equal(o, g) for o in outs)
+    check_reduce(xs, bits, 128, SR, f"workload 5 b{bits} N8")

@@ -1,0 +1,152 @@
+"""CPU tests of the library's host logic and of the integer/float building blocks its kernels use.
+
+No GPU and no compute calls: the C-ABI library is loaded only to check its exports and its host-only
+fcv2_get_layout; the building blocks (csrc/fcv2_bits.h) are compiled for the host and held to the oracle.
+"""
+import ctypes as C
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+import oracle as O
+from paper_2508_03760_amd import build as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2508_03760_amd", "csrc")
+
+
+@pytest.fixture(scope="module")
+def hc():
+    so = os.path.join(CSRC, "libfcv2_hostcheck.so")
+    src = os.path.join(CSRC, "fcv2_hostcheck.cpp")
+    newest = max(os.path.getmtime(src), os.path.getmtime(os.path.join(CSRC, "fcv2_bits.h")))
+    if not os.path.exists(so) or os.path.getmtime(so) < newest:
+        subprocess.run(["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fPIC", "-shared", "-o", so, src], check=True)
+    L = C.CDLL(so)
+    L.hc_div_mismatches.restype = C.c_uint64
+    L.hc_div_mismatches.argtypes = [C.c_int, C.c_uint32, C.c_uint32]
+    for f in ("hc_key_of_bf16", "hc_bf16_of_key", "hc_bf16_rne_bits", "hc_bf16_round_up_bits"):
+        getattr(L, f).restype = C.c_uint32
+        getattr(L, f).argtypes = [C.c_uint32]
+    return L
+
+
+@pytest.fixture(scope="module")
+def lib():
+    path = B.lib_path()
+    if not os.path.exists(path):
+        B.build()
+    return C.CDLL(path)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "fcv2.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(fcv2_[a-z_0-9]+)\s*\(", header))
+    assert names >= {"fcv2_get_layout", "fcv2_quantize_pack", "fcv2_unpack_dequant", "fcv2_reduce_requant",
+                     "fcv2_dispatch_workspace_bytes", "fcv2_dispatch_quant", "fcv2_status_string", "fcv2_version"}
+    for n in names:
+        assert hasattr(lib, n), n
+    lib.fcv2_status_string.restype = C.c_char_p
+    assert lib.fcv2_status_string(0) == b"ok" and lib.fcv2_version() >= 100
+
+
+def test_get_layout_matches_oracle_and_rejects_bad_input(lib):
+    from paper_2508_03760_amd import fcv2
+    for bits in range(2, 9):
+        for group in (32, 64, 128, 256):
+            for flags in (0, 1, 2, 3):
+                for align in (16, 256):
+                    for n in (group, 4096, 7168 * 4):
+                        if n % group:
+                            continue
+                        a = fcv2.get_layout(n, bits, group, flags, align)
+                        b = O.get_layout(n, bits, group, flags, align)
+                        assert a.__dict__ == b.__dict__
+    with pytest.raises(fcv2.Fcv2Error):
+        fcv2.get_layout(4096, 9, 128, 1)
+    with pytest.raises(fcv2.Fcv2Error):
+        fcv2.get_layout(4096, 4, 48, 1)
+    with pytest.raises(fcv2.Fcv2Error):
+        fcv2.get_layout(4100, 4, 128, 1)
+    with pytest.raises(fcv2.Fcv2Error):
+        fcv2.get_layout(0, 4, 128, 1)
+    with pytest.raises(fcv2.Fcv2Error):
+        fcv2.get_layout(4096, 4, 128, 8)
+    with pytest.raises(fcv2.Fcv2Error):
+        fcv2.get_layout(4096, 4, 128, 1, 48)
+    assert fcv2.dispatch_workspace_bytes(8192, 8, 256) > 8192 * 8 * 4
+
+
+def test_null_and_misaligned_arguments_are_refused_on_the_host(lib):
+    from paper_2508_03760_amd.fcv2 import _Fmt
+    fmt = _Fmt(4, 128, 1)
+    vp = C.c_void_p
+    lib.fcv2_quantize_pack.argtypes = [vp, C.c_uint64, C.POINTER(_Fmt), vp, vp]
+    assert lib.fcv2_quantize_pack(None, 4096, C.byref(fmt), vp(256), None) == -1
+    assert lib.fcv2_quantize_pack(vp(256), 4096, C.byref(fmt), vp(264), None) == -3  # not 16-byte aligned
+    assert lib.fcv2_quantize_pack(vp(256), 4000, C.byref(fmt), vp(512), None) == -1
+    lib.fcv2_reduce_requant.argtypes = [C.POINTER(vp), C.c_int, C.c_uint64, C.POINTER(_Fmt), C.POINTER(_Fmt), vp, vp, vp]
+    peers = (vp * 2)(256, 512)
+    assert lib.fcv2_reduce_requant(peers, 0, 4096, C.byref(fmt), C.byref(fmt), vp(1024), None, None) == -1
+    assert lib.fcv2_reduce_requant(peers, 17, 4096, C.byref(fmt), C.byref(fmt), vp(1024), None, None) == -1
+    other = _Fmt(5, 128, 1)
+    assert lib.fcv2_reduce_requant(peers, 2, 4096, C.byref(fmt), C.byref(other), vp(1024), None, None) == -2
+    lib.fcv2_dispatch_quant.argtypes = [vp, vp, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(_Fmt), vp, vp,
+                                        vp, vp, C.c_size_t, vp]
+    assert lib.fcv2_dispatch_quant(vp(256), vp(256), 64, 512, 4, 16, C.byref(fmt), vp(256), vp(256), vp(256), vp(256), 16,
+                                   None) == -4  # workspace too small
+
+
+@pytest.mark.parametrize("bits", range(2, 9))
+def test_plane_packing_sequences_match_oracle(hc, bits):
+    rng = np.random.default_rng(bits)
+    cases = [rng.integers(0, 2 ** bits, 8).astype(np.uint8) for _ in range(300)]
+    cases += [np.full(8, 2 ** bits - 1, np.uint8), np.zeros(8, np.uint8)]
+    cases += [np.eye(8, dtype=np.uint8)[i] * (2 ** bits - 1) for i in range(8)]
+    for codes in cases:
+        out = (C.c_uint32 * 5)()
+        assert hc.hc_planes_of_codes(bits, codes.ctypes.data_as(C.POINTER(C.c_uint8)), out) == 0
+        L = O.get_layout(8, bits, 8, 0, align=1)
+        packed = O.split_pack(codes, bits, 8, 0, align=1)
+        want = {}
+        for w, nbytes in ((8, 8), (4, 4), (2, 2), (1, 1)):
+            off = getattr(L, f"off_plane{w}")
+            want[w] = None if off == O.ABSENT else int.from_bytes(packed[off:off + nbytes].tobytes(), "little")
+        if want[8] is not None:
+            assert out[0] | (out[1] << 32) == want[8]
+        for w, got in ((4, out[2]), (2, out[3]), (1, out[4])):
+            if want[w] is not None:
+                assert got == want[w], (bits, w, codes)
+        if bits < 8:  # and back
+            back = np.zeros(8, np.uint8)
+            assert hc.hc_codes_of_planes(bits, out[2], out[3], out[4], back.ctypes.data_as(C.POINTER(C.c_uint8))) == 0
+            assert np.array_equal(back, codes)
+
+
+def test_bf16_helpers_match_oracle(hc):
+    for u in range(0, 65536, 7):
+        assert hc.hc_key_of_bf16(u) == O.key(u)
+        assert hc.hc_bf16_of_key(hc.hc_key_of_bf16(u)) == u
+    rng = np.random.default_rng(0)
+    vals = rng.standard_normal(3000).astype(np.float32) * np.float32(10.0) ** rng.integers(-8, 8, 3000).astype(np.float32)
+    for v in np.concatenate([vals, np.array([0.0, -0.0, np.inf, -np.inf, np.nan, 1.00390625, 1.01171875], np.float32)]):
+        u = int(np.float32(v).view(np.uint32))
+        assert hc.hc_bf16_rne_bits(u) == O.bf16_rne(v)
+    for u in (0x3F800000, 0x3F800001, 0x3F80FFFF, 0x3F810000, 0x00810000):
+        r = hc.hc_bf16_round_up_bits(u)
+        assert r >= u and r & 0xFFFF == 0 and r - u < 0x10000
+
+
+@pytest.mark.parametrize("qmax", [3, 7, 15, 31, 63, 127, 255])
+def test_short_division_is_ieee_division(hc, qmax):
+    # every significand of one binade (scaling by powers of two is exact), plus the ranges where the exponent
+    # matters: around the 2^-64 threshold of the codec, the largest finite values, denormal quotients, inf
+    assert hc.hc_div_mismatches(qmax, 0x3F800000, 1 << 23) == 0
+    assert hc.hc_div_mismatches(qmax, 0x1F000000, 1 << 21) == 0
+    assert hc.hc_div_mismatches(qmax, 0x7F000000, 0x00800001) == 0  # up to and including +inf
+    assert hc.hc_div_mismatches(qmax, 0x00000000, 1 << 20) == 0
+    assert hc.hc_div_mismatches(qmax, 0x00800000, 1 << 22) == 0

@@ -98,7 +98,7 @@ def test_layout_sections(bits, group):
             for off, size in secs:  # in order, aligned, not overlapping, padding < align
                 assert off % align == 0 and end <= off < end + align
                 end = off + size
-            assert L.total_bytes == end
+            assert L.total_bytes == -(-end // align) * align
 
 
 # ---- order key ----------------------------------------------------------------------------------------------
