@@ -1,0 +1,234 @@
+"""Benchmark of libfcv2 on one MI355X.
+
+One "step" is one pass of the whole codec hot path over the Llama-3-8B-shaped AllReduce payload
+(bf16 [4096 x 4096], 3-bit = 2+1 split, group 128, spike reserving, 8 simulated peer chunks):
+    fcv2_quantize_pack(x)  ->  fcv2_reduce_requant(8 packed peer chunks)  ->  fcv2_unpack_dequant(result, bf16)
+i.e. the three kernels one rank runs locally in a two-step quantized AllReduce.  All inputs are resident in HBM
+before the timed region.  Buffer sets are rotated so that every step reads lines that are not in the 256 MB
+last-level cache (the whole working set of one step is smaller than that cache).
+
+Prints ONE JSON line.  `value` = algorithmic bytes of a step / time of a step (effective HBM GB/s).
+Extra keys: per-kernel figures, a sweep over bit widths 2..8, the dispatch workload, the roofline of the
+dominant kernel and the CPU oracle timed beside it.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+LLC_BYTES = 256 << 20
+
+
+def packed_bytes(n, bits, group, spike=True):
+    """Algorithmic size of a packed record: planes + per-group metadata (no alignment padding)."""
+    return n * bits // 8 + (10 if spike else 4) * (n // group)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-sweep", action="store_true", help="skip the bit-width sweep and the dispatch workload")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2508_03760_amd import fcv2
+    from paper_2508_03760_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    fcv2.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    SR = fcv2.F_SPIKE
+    w = W.WORKLOADS[2]
+    rows, cols, n_peers, group = w["rows"], w["cols"], w["peers"], 128
+    n = rows * cols
+
+    def bf16(a):
+        return torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
+
+    xs_host = [W.tensor(2, p).reshape(-1) for p in range(n_peers)]
+    xs = [bf16(x) for x in xs_host]
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def make_sets(bits, n_sets):
+        """n_sets independent copies of (x, 8 packed peers, outputs) at different addresses."""
+        L = fcv2.get_layout(n, bits, group, SR)
+        sets = []
+        for _ in range(n_sets):
+            peers = [fcv2.quantize_pack(x, bits, group, SR) for x in xs]
+            sets.append(dict(x=xs[0].clone(), peers=peers,
+                             q=torch.zeros(L.total_bytes, dtype=torch.uint8, device=dev),
+                             r=torch.zeros(L.total_bytes, dtype=torch.uint8, device=dev),
+                             o=torch.empty(n, dtype=torch.bfloat16, device=dev)))
+        torch.cuda.synchronize()
+        return sets
+
+    def algo_bytes(bits):
+        P = packed_bytes(n, bits, group)
+        return dict(quantize_pack=2 * n + P, reduce_requant=(n_peers + 1) * P, unpack_dequant=P + 2 * n)
+
+    def n_sets_for(bits):
+        per_set = 2 * n * 2 + (n_peers + 2) * packed_bytes(n, bits, group)
+        return max(4, -(-3 * LLC_BYTES // per_set))
+
+    def run_steps(sets, bits, steps, warmup, per_kernel):
+        """Times `steps` steps after `warmup`; returns (ms per step, {kernel: ms per launch})."""
+        import ctypes as C
+        lib = fcv2.lib()
+        fmt = fcv2._Fmt(bits, group, SR)
+        stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        # arguments marshalled once per buffer set: the timed loop is three C-ABI calls per step and nothing else
+        for s in sets:
+            if s.get("bits") != bits:
+                arr = (C.c_void_p * n_peers)(*[p.data_ptr() for p in s["peers"]])
+                s["bits"] = bits
+                s["keep"] = (arr, fmt)
+                s["calls"] = (
+                    (lib.fcv2_quantize_pack, (C.c_void_p(s["x"].data_ptr()), n, C.byref(fmt), C.c_void_p(s["q"].data_ptr()), stream)),
+                    (lib.fcv2_reduce_requant, (arr, n_peers, n, C.byref(fmt), C.byref(fmt), C.c_void_p(s["r"].data_ptr()), None, stream)),
+                    (lib.fcv2_unpack_dequant, (C.c_void_p(s["r"].data_ptr()), n, C.byref(fmt), C.c_void_p(s["o"].data_ptr()), fcv2.DT_BF16, stream)),
+                )
+
+        def step(s, marks=None):
+            for k, (fn, a) in enumerate(s["calls"]):
+                if marks is not None:
+                    marks[k].record()
+                rc = fn(*a)
+                if rc != 0:
+                    raise RuntimeError(f"libfcv2 call {k} failed: {rc}")
+            if marks is not None:
+                marks[3].record()
+
+        for i in range(warmup):
+            step(sets[i % len(sets)])
+        torch.cuda.synchronize()
+        marks = [[ev() for _ in range(4)] for _ in range(steps)] if per_kernel else None
+        t0, t1 = ev(), ev()
+        t0.record()
+        for i in range(steps):
+            step(sets[i % len(sets)], marks[i] if per_kernel else None)
+        t1.record()
+        torch.cuda.synchronize()
+        ms = t0.elapsed_time(t1) / steps
+        kern = {}
+        if per_kernel:
+            for k, name in enumerate(("quantize_pack", "reduce_requant", "unpack_dequant")):
+                kern[name] = sum(m[k].elapsed_time(m[k + 1]) for m in marks) / steps
+        return ms, kern
+
+    # ---- headline: 3-bit ------------------------------------------------------------------------------------
+    bits = 3
+    sets = make_sets(bits, n_sets_for(bits))
+    ms_step, _ = run_steps(sets, bits, args.steps, args.warmup, per_kernel=False)  # the timed region proper
+    _, kern_ms = run_steps(sets, bits, args.steps, 2, per_kernel=True)             # same loop with per-kernel marks
+    ab = algo_bytes(bits)
+    total_bytes = sum(ab.values())
+    value = total_bytes / (ms_step * 1e-3) / 1e9
+    kernels = {k: dict(ms=round(kern_ms[k], 5), algorithmic_bytes=ab[k],
+                       gbs=round(ab[k] / (kern_ms[k] * 1e-3) / 1e9, 1),
+                       frac_of_hbm_peak=round(ab[k] / (kern_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)) for k in ab}
+    dom = "reduce_requant"
+    roofline = dict(bound="hbm", kernel=f"k_reduce_requant<3,16,true> ({dom}, N={n_peers})",
+                    achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(kernels[dom]["gbs"] / HBM_PEAK_GBS, 4), traffic=None)
+    # warm-cache figure for context: one buffer set, everything stays in the last-level cache
+    ms_warm, _ = run_steps(sets[:1], bits, args.steps, args.warmup, per_kernel=False)
+    del sets
+    torch.cuda.empty_cache()
+
+    # ---- sweep over bit widths, and the dispatch workload -----------------------------------------------------
+    sweep, dispatch = {}, None
+    if not args.no_sweep:
+        for b in (2, 3, 4, 5, 6, 7, 8):
+            s = make_sets(b, n_sets_for(b))
+            ms_b, k_b = run_steps(s, b, max(10, args.steps // 2), 3, per_kernel=True)
+            abb = algo_bytes(b)
+            sweep[str(b)] = {k: dict(us=round(k_b[k] * 1e3, 2), gbs=round(abb[k] / (k_b[k] * 1e-3) / 1e9, 1),
+                                     frac=round(abb[k] / (k_b[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)) for k in abb}
+            sweep[str(b)]["step_gbs"] = round(sum(abb.values()) / (ms_b * 1e-3) / 1e9, 1)
+            del s
+            torch.cuda.empty_cache()
+        w3 = W.WORKLOADS[3]
+        T, H, E, K = w3["rows"], w3["cols"], w3["experts"], w3["topk"]
+        x3 = bf16(W.tensor(3, 0).reshape(-1)).view(T, H)
+        ids = torch.from_numpy(W.topk_routing(W.seed_for(3), T, E, K)).to(dev)
+        L3 = fcv2.get_layout(H, 2, 128, SR, fcv2.ROW_ALIGN)
+        bufs = [dict(send=torch.zeros((T * K, L3.total_bytes), dtype=torch.uint8, device=dev),
+                     offs=torch.zeros(E + 1, dtype=torch.int32, device=dev),
+                     src=torch.zeros(T * K, dtype=torch.int32, device=dev),
+                     ws=torch.empty(fcv2.dispatch_workspace_bytes(T, K, E), dtype=torch.uint8, device=dev),
+                     x=x3.clone()) for _ in range(4)]
+
+        def disp(bf):
+            fcv2.dispatch_quant(bf["x"], ids, E, 2, 128, SR, send_buf=bf["send"], expert_offsets=bf["offs"],
+                                row_src=bf["src"], workspace=bf["ws"])
+
+        for i in range(3):
+            disp(bufs[i % 4])
+        torch.cuda.synchronize()
+        t0, t1 = ev(), ev()
+        reps = max(10, args.steps // 4)
+        t0.record()
+        for i in range(reps):
+            disp(bufs[i % 4])
+        t1.record()
+        torch.cuda.synchronize()
+        ms_d = t0.elapsed_time(t1) / reps
+        R = T * K
+        bytes_d = 2 * T * H + 4 * T * K + R * packed_bytes(H, 2, 128) + 4 * (E + 1) + 4 * R
+        dispatch = dict(workload=W.WORKLOADS[3]["name"], ms=round(ms_d, 4), algorithmic_bytes=bytes_d,
+                        gbs=round(bytes_d / (ms_d * 1e-3) / 1e9, 1),
+                        frac_of_hbm_peak=round(bytes_d / (ms_d * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
+        del bufs, x3
+        torch.cuda.empty_cache()
+
+    # ---- the CPU oracle on the same workload, timed on the host -------------------------------------------------
+    cpu = None
+    if not args.no_cpu:
+        import oracle as O
+        fmt = (3, group, SR)
+        reps = 3
+        peers_o = [O.quantize_pack(x, *fmt) for x in xs_host]  # untimed set-up of the peer chunks
+        t = time.perf_counter()
+        for _ in range(reps):
+            O.quantize_pack(xs_host[0], *fmt)
+            r = O.reduce_requant(peers_o, n, fmt)
+            O.unpack_dequant(r, n, *fmt, O.DT_BF16)
+        dt = (time.perf_counter() - t) / reps
+        cpu = dict(value=round(total_bytes / dt / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
+                   sample=f"{reps} full steps of the same workload (quantize_pack + reduce_requant N=8 + unpack_dequant "
+                          f"on 4096x4096, 3-bit), {dt:.2f} s per step on one host thread")
+
+    out = {
+        "metric": "effective HBM GB/s (and % of peak) for quantize_pack + reduce_requant, bits 2-8",
+        "value": round(value, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": W.WORKLOADS[2]["name"] + "_b3_g128_sr_N8", "elements": n, "bits": 3, "group": 128,
+                   "spike_reserving": True, "peers": n_peers, "step": "quantize_pack + reduce_requant + unpack_dequant",
+                   "buffer_sets_rotated": n_sets_for(3)},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "warm_cache_gbs": round(total_bytes / (ms_warm * 1e-3) / 1e9, 1),
+        "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
