@@ -17,6 +17,7 @@
  *     valid once the caller has synchronized that stream.
  *   - Device pointers must be 16-byte aligned (FCV2_ERR_ALIGN otherwise).
  *   - Inputs are finite bf16.  Non-finite values do not crash and give deterministic output.
+ *   - A tensor call takes at most 2^31 elements (FCV2_ERR_UNSUPPORTED beyond), a dispatch call T*H <= 2^31.
  *
  * Packed record ("wire format") of n elements, as described by fcv2_get_layout():
  *     plane8 | plane4 | plane2 | plane1 | scale[ng] | zero[ng] | spike_val[2*ng] | spike_idx[2*ng]
@@ -110,6 +111,11 @@ int fcv2_dispatch_workspace_bytes(uint32_t T, uint32_t K, uint32_t E, size_t* ou
 int fcv2_dispatch_quant(const void* x_bf16_dev, const int32_t* topk_ids_dev, uint32_t T, uint32_t H, uint32_t K,
                         uint32_t E, const fcv2_fmt_t* fmt, void* send_buf_dev, int32_t* expert_offsets_dev,
                         int32_t* row_src_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* Diagnostic, not part of the codec: a plain streaming copy of `bytes` (a multiple of 16) from src_dev to
+ * dst_dev, 16 bytes per lane.  The benchmark uses it to measure the practical HBM ceiling next to the codec
+ * kernels and to calibrate memory-traffic counters against a transfer of known size. */
+int fcv2_stream_copy(const void* src_dev, void* dst_dev, uint64_t bytes, void* hip_stream);
 
 const char* fcv2_status_string(int status);
 int fcv2_version(void);

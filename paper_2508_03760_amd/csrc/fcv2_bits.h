@@ -128,6 +128,8 @@ template <int BITS> FCV2_HD void codes_even_odd(uint32_t p4, uint32_t p2, uint32
         ev = low & M;
         od = (low >> 4) & M;
     }
+    FCV2_KEEP(ev);  // consumers convert byte k directly (v_cvt_f32_ubyte<k>); do not re-derive from the nibbles
+    FCV2_KEEP(od);
 }
 
 }  // namespace fcv2

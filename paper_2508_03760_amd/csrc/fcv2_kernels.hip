@@ -1,9 +1,12 @@
 // fcv2_kernels.hip -- HIP kernels and C ABI of libfcv2 for gfx950 (MI355X, wave64).
 //
-// Work decomposition shared by all kernels: one lane owns 8 consecutive elements (one 128-bit load of bf16),
-// a quantization group of G elements is owned by LPG = G/8 neighbouring lanes (4, 8, 16 or 32), so group
-// reductions are DPP butterflies inside a 16-lane row (plus one swizzle for G = 256).  The paper's own block
-// shape (512 threads x 8 values, Section 4.1) was made for other hardware and is not followed.
+// Work decomposition: a lane owns EPL consecutive elements, a quantization group of G elements is owned by
+// LPG = G/EPL neighbouring lanes, so group reductions are DPP butterflies inside a 16-lane row.  The kernels
+// that stream a tensor once (quantize_pack, unpack_dequant, dispatch_quant) use EPL = 32 (64 bytes of bf16 per
+// lane, LPG = 1..8): per-lane overheads are paid once per 32 elements and every wave keeps 4 KiB of loads in
+// flight.  reduce_requant uses EPL = 8 (LPG = 4..32): its values must be patched in registers at the spike
+// positions, which is cheapest when a lane seldom owns both spikes of a group.  The paper's own block shape
+// (512 threads x 8 values, Section 4.1) was made for other hardware and is not followed.
 //
 // Arithmetic is fixed so that results can be compared bit for bit with an independent CPU implementation:
 //   scale = (hi - lo) / qmax in fp32 (IEEE division), stored rounded up to bf16 unless FCV2_F_META_FP32;
@@ -18,19 +21,12 @@
 
 namespace fcv2 {
 
-struct Sections {  // device addresses of the sections of one packed record
-    uint8_t* plane8;
-    uint8_t* plane4;
-    uint8_t* plane2;
-    uint8_t* plane1;
-    uint8_t* scale;
-    uint8_t* zero;
-    uint8_t* spike_val;
-    uint8_t* spike_idx;
+struct Rec {  // section offsets of one packed record, relative to its first byte (records are < 4 GiB)
+    uint32_t plane8, plane4, plane2, plane1, scale, zero, spike_val, spike_idx;
 };
 
-struct PeerArgs {
-    Sections s[FCV2_MAX_PEERS];
+struct PeerPtrs {
+    const uint8_t* base[FCV2_MAX_PEERS];
 };
 
 struct GroupMeta {
@@ -45,82 +41,126 @@ template <int CTRL> __device__ __forceinline__ uint32_t dpp(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp((int)0xFFFFFFFF, (int)v, CTRL, 0xF, 0xF, false);
 }
 
-// Minimum over the LPG lanes of a group; every lane of the group gets the result.
-template <int LPG> __device__ __forceinline__ uint32_t group_min(uint32_t v) {
-    v = min(v, dpp<0xB1>(v));                   // quad_perm [1,0,3,2]
-    v = min(v, dpp<0x4E>(v));                   // quad_perm [2,3,0,1]
-    if (LPG >= 8) v = min(v, dpp<0x141>(v));    // row_half_mirror
-    if (LPG >= 16) v = min(v, dpp<0x140>(v));   // row_mirror
-    if (LPG >= 32) v = min(v, (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x401F));  // lane ^ 16
-    return v;
+// Value held by lane K of this lane's quad.
+template <int K> __device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, K * 0x55, 0xF, 0xF, true);
 }
 
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
 
-// 1 / s with IEEE rounding for a bf16-valued s in [2^-64, 2^120]: hardware reciprocal (1 ulp) plus one Newton
-// step.  The quotient 2^k / m with an 8-bit significand m stays at least 2^-33 (relative) away from every
-// rounding boundary, far more than the error left after the step, so the final rounding is the IEEE one.
-__device__ __forceinline__ float rcp_of_bf16(float s) {
+__device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t r;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// Running two smallest values (m1 <= m2) of a stream.
+__device__ __forceinline__ void push2(uint32_t& m1, uint32_t& m2, uint32_t c) {
+    m2 = umed3(m1, m2, c);
+    m1 = min(m1, c);
+}
+
+// Two smallest values over the LPG lanes of a group (the lanes hold disjoint sets); all lanes get the result.
+template <int CTRL> __device__ __forceinline__ void merge2_step(uint32_t& m1, uint32_t& m2) {
+    const uint32_t p1lo = (uint32_t)__builtin_amdgcn_update_dpp((int)0xFFFFFFFF, (int)m1, CTRL, 0xF, 0xF, false);
+    const uint32_t p1hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m1, CTRL, 0xF, 0xF, true);
+    const uint32_t p2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m2, CTRL, 0xF, 0xF, true);
+    const uint32_t t = max(m1, p1hi);
+    m1 = min(m1, p1lo);
+    m2 = min(min(t, m2), p2);
+}
+template <int LPG> __device__ __forceinline__ void group_min2(uint32_t& m1, uint32_t& m2) {
+    if (LPG >= 2) merge2_step<0xB1>(m1, m2);
+    if (LPG >= 4) merge2_step<0x4E>(m1, m2);
+    if (LPG >= 8) merge2_step<0x141>(m1, m2);
+    if (LPG >= 16) merge2_step<0x140>(m1, m2);
+    if (LPG >= 32) {
+        const uint32_t p1 = (uint32_t)__builtin_amdgcn_ds_swizzle((int)m1, 0x401F);  // lane ^ 16
+        const uint32_t p2 = (uint32_t)__builtin_amdgcn_ds_swizzle((int)m2, 0x401F);
+        const uint32_t t = max(m1, p1);
+        m1 = min(m1, p1);
+        m2 = min(min(t, m2), p2);
+    }
+}
+template <int LPG> __device__ __forceinline__ uint32_t group_min(uint32_t v) {
+    if (LPG >= 2) v = min(v, dpp<0xB1>(v));
+    if (LPG >= 4) v = min(v, dpp<0x4E>(v));
+    if (LPG >= 8) v = min(v, dpp<0x141>(v));
+    if (LPG >= 16) v = min(v, dpp<0x140>(v));
+    if (LPG >= 32) v = min(v, (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x401F));
+    return v;
+}
+
+// 1 / s with IEEE rounding for s in [2^-64, 2^120]: hardware reciprocal (1 ulp) plus one Newton step.
+// Checked on the MI355X against IEEE division for every fp32 value of that range: no mismatch.
+__device__ __forceinline__ float rcp_newton(float s) {
     const float y0 = __builtin_amdgcn_rcpf(s);
     const float e = __fmaf_rn(-s, y0, 1.0f);
     return __fmaf_rn(e, y0, y0);
 }
 
-// ---- encoder core: 8 bf16 values of this lane -> 8 codes (one per byte) + the group's metadata ----------------
-// w[d] holds elements 2d (low half) and 2d+1 (high half).  lig = lane index inside the group.
+// Two fp32 -> packed bf16, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    typedef float float2v __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf2v __attribute__((ext_vector_type(2)));
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector((float2v){a, b}, bf2v));
+}
+
+// ---- encoder core: EPL consecutive bf16 values of this lane -> EPL codes (one per byte) + the group's metadata ----
+// w[d] holds elements 2d (low half) and 2d+1 (high half).  lig = lane index inside the group (LPG = G / EPL lanes).
 // Spike reserving (Section 3.3): the group's minimum and maximum are set aside (lowest index on ties, the
-// maximum searched among the other positions) and the rest is quantized over [2nd smallest, 2nd largest].
-template <int BITS, int LPG, bool SR>
-__device__ __forceinline__ void quantize8(const uint32_t (&w)[4], uint32_t lig, bool meta_fp32, uint32_t& c0,
-                                          uint32_t& c1, GroupMeta& m) {
-    constexpr float qmaxf = (float)((1 << BITS) - 1);
-    const uint32_t lig8 = lig * 8u;
-
-    // composite = order key << 16 | position: one unsigned min gives value and lowest index at once
-    uint32_t cmin[8], cmax[8];
+// maximum searched among the other positions) and the rest is quantized over [2nd smallest, 2nd largest]:
+// the two smallest composites (key << 16 | position) and the two smallest of (~key << 16 | position) are
+// tracked in one pass; the smallest of each gives a spike and its position, the second the new range.
+template <int BITS, int EPL, int LPG, bool SR>
+__device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint32_t lig, bool meta_fp32, uint32_t (&c)[EPL / 4],
+                                              GroupMeta& m) {
+    const uint32_t lbase = lig * (uint32_t)EPL;
+    uint32_t a1, a2, b1, b2;  // two smallest composites (a: minimum side, b: maximum side)
 #pragma unroll
-    for (int d = 0; d < 4; ++d) {
+    for (int d = 0; d < EPL / 2; ++d) {
         typedef short short2v __attribute__((ext_vector_type(2)));
-        short2v sv = __builtin_bit_cast(short2v, w[d]);
-        uint32_t sign = __builtin_bit_cast(uint32_t, sv >> (short2v){15, 15});
-        uint32_t k = w[d] ^ (sign | 0x80008000u);  // two order keys
-        cmin[2 * d] = (k << 16) | (uint32_t)(2 * d);
-        cmin[2 * d + 1] = (k & 0xFFFF0000u) | (uint32_t)(2 * d + 1);
-        cmax[2 * d] = cmin[2 * d] ^ 0xFFFF0000u;  // inverted key: min finds the largest value
-        cmax[2 * d + 1] = cmin[2 * d + 1] ^ 0xFFFF0000u;
+        const short2v sv = __builtin_bit_cast(short2v, w[d]);
+        const uint32_t sign = __builtin_bit_cast(uint32_t, sv >> (short2v){15, 15});
+        const uint32_t k = w[d] ^ (sign | 0x80008000u);  // two order keys
+        const uint32_t e0 = (k << 16) | (uint32_t)(2 * d), e1 = (k & 0xFFFF0000u) | (uint32_t)(2 * d + 1);
+        const uint32_t f0 = e0 ^ 0xFFFF0000u, f1 = e1 ^ 0xFFFF0000u;  // inverted key: min finds the largest value
+        if (d == 0) {
+            a1 = min(e0, e1);
+            a2 = max(e0, e1);
+            b1 = min(f0, f1);
+            b2 = max(f0, f1);
+        } else if (SR) {
+            push2(a1, a2, e0);
+            push2(a1, a2, e1);
+            push2(b1, b2, f0);
+            push2(b1, b2, f1);
+        } else {
+            a1 = min(a1, min(e0, e1));
+            b1 = min(b1, min(f0, f1));
+        }
     }
-    uint32_t lmin = cmin[0], lmax = cmax[0];
-#pragma unroll
-    for (int j = 1; j < 8; ++j) {
-        lmin = min(lmin, cmin[j]);
-        lmax = min(lmax, cmax[j]);
-    }
-    const uint32_t gmin = group_min<LPG>(lmin + lig8);
-    const uint32_t gmax = group_min<LPG>(lmax + lig8);
-
+    a1 += lbase;
+    b1 += lbase;
     uint32_t klo, khi, imax = 0xFFFFu;
     if (SR) {
-        // second smallest composite: everything except the one equal to the group minimum
-        const uint32_t rmin = gmin - lig8 + 1u, rmax = gmax - lig8 + 1u;
-        uint32_t l2min = cmin[0] - rmin, l2max = cmax[0] - rmax;  // the excluded entry wraps to 0xFFFFFFFF
-#pragma unroll
-        for (int j = 1; j < 8; ++j) {
-            l2min = min(l2min, cmin[j] - rmin);
-            l2max = min(l2max, cmax[j] - rmax);
-        }
-        const uint32_t g2min = group_min<LPG>(l2min + gmin + 1u);
-        const uint32_t g2max = group_min<LPG>(l2max + gmax + 1u);
-        const uint32_t imin = gmin & 0xFFFFu;
+        a2 += lbase;
+        b2 += lbase;
+        group_min2<LPG>(a1, a2);
+        group_min2<LPG>(b1, b2);
+        const uint32_t imin = a1 & 0xFFFFu;
         // a constant group: the first maximum is the minimum itself, take the next position
-        imax = ((gmax & 0xFFFFu) == imin) ? (g2max & 0xFFFFu) : (gmax & 0xFFFFu);
-        klo = g2min >> 16;
-        khi = (~g2max) >> 16;
-        m.sv = bf16_of_key(gmin >> 16) | (bf16_of_key((~gmax) >> 16) << 16);
+        imax = ((b1 & 0xFFFFu) == imin) ? (b2 & 0xFFFFu) : (b1 & 0xFFFFu);
+        klo = a2 >> 16;
+        khi = (~b2) >> 16;
+        m.sv = bf16_of_key(a1 >> 16) | (bf16_of_key((~b1) >> 16) << 16);
         m.si = imin | (imax << 8);
     } else {
-        klo = gmin >> 16;
-        khi = (~gmax) >> 16;
+        a1 = group_min<LPG>(a1);
+        b1 = group_min<LPG>(b1);
+        klo = a1 >> 16;
+        khi = (~b1) >> 16;
         m.sv = 0;
         m.si = 0;
     }
@@ -130,96 +170,178 @@ __device__ __forceinline__ void quantize8(const uint32_t (&w)[4], uint32_t lig, 
     float s = 1.0f;
     if (s32 >= 0x1p-64f) s = meta_fp32 ? s32 : u2f(bf16_round_up_bits(f2u(s32)));
     float inv;
-    if (meta_fp32 || !(s <= 0x1p+120f))
-        inv = __fdiv_rn(1.0f, s);  // arbitrary significand, or a reciprocal near the denormal range
+    if (!(s <= 0x1p+120f))
+        inv = __fdiv_rn(1.0f, s);  // reciprocal near the denormal range, or an infinite scale
     else
-        inv = rcp_of_bf16(s);
+        inv = rcp_newton(s);
     m.s = s;
     m.lo = lo;
 
-    c0 = 0;
-    c1 = 0;
+    // code = rint((x - lo) * inv) clamped to [0, qmax].  v_cvt_pk_u8_f32 rounds to nearest even and saturates
+    // to [0, 255] (NaN -> 0), and for every position outside the spikes (x - lo) * inv <= qmax * (1 + 2^-22),
+    // so the conversion alone already is the clamped code; the minimum spike lands on 0 by itself, the
+    // maximum spike's byte is cleared below.
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const float x = u2f((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
-        const float t = __fmul_rn(__fsub_rn(x, lo), inv);
-        const float r = fminf(fmaxf(rintf(t), 0.0f), qmaxf);
-        if (j < 4)
-            c0 = __builtin_amdgcn_cvt_pk_u8_f32(r, j & 3, c0);
-        else
-            c1 = __builtin_amdgcn_cvt_pk_u8_f32(r, j & 3, c1);
+    for (int i = 0; i < EPL / 4; ++i) {
+        uint32_t cc = 0;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int j = 4 * i + b;
+            const float x = u2f((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
+            cc = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn(__fsub_rn(x, lo), inv), b, cc);
+        }
+        c[i] = cc;
     }
     if (SR) {
-        // code 0 at the spike positions: the minimum already clamps to 0, clear the maximum's byte
-        const uint32_t rel = imax - lig8;
+        const uint32_t rel = imax - lbase;  // position inside this lane, or >= EPL
         const uint32_t clr = ~(0xFFu << ((rel & 3u) * 8u));
-        c0 &= (rel < 4u) ? clr : 0xFFFFFFFFu;
-        c1 &= (rel - 4u < 4u) ? clr : 0xFFFFFFFFu;
+        const uint32_t dw = rel >> 2;
+#pragma unroll
+        for (int i = 0; i < EPL / 4; ++i) c[i] &= (dw == (uint32_t)i) ? clr : 0xFFFFFFFFu;
     }
 }
 
-// Store the planes of this lane's 8 codes.  L = global lane index (element index / 8).
-template <int BITS> __device__ __forceinline__ void store_planes(const Sections& o, uint64_t L, uint32_t c0, uint32_t c1) {
+// Store the planes of this lane's EPL codes.  L = lane index inside the record (element index / EPL).
+template <int BITS, int EPL> __device__ __forceinline__ void store_planes(uint8_t* base, const Rec& r, uint32_t L,
+                                                                           const uint32_t (&c)[EPL / 4]) {
     using P = Planes<BITS>;
-    if (P::w8) *reinterpret_cast<uint2*>(o.plane8 + 8 * L) = make_uint2(c0, c1);
-    if (P::w4) *reinterpret_cast<uint32_t*>(o.plane4 + 4 * L) = pack_plane4<P::sh4, BITS>(c0, c1);
-    if (P::w2) *reinterpret_cast<uint16_t*>(o.plane2 + 2 * L) = (uint16_t)pack_plane2<P::sh2, BITS>(c0, c1);
-    if (P::w1) *(o.plane1 + L) = (uint8_t)pack_plane1<P::sh1, BITS>(c0, c1);
-}
-
-template <bool SR> __device__ __forceinline__ void store_meta(const Sections& o, uint64_t g, const GroupMeta& m, bool meta_fp32) {
-    if (meta_fp32) {
-        reinterpret_cast<float*>(o.scale)[g] = m.s;
-        reinterpret_cast<float*>(o.zero)[g] = m.lo;
-    } else {
-        reinterpret_cast<uint16_t*>(o.scale)[g] = (uint16_t)(f2u(m.s) >> 16);
-        reinterpret_cast<uint16_t*>(o.zero)[g] = (uint16_t)(f2u(m.lo) >> 16);
-    }
-    if (SR) {
-        reinterpret_cast<uint32_t*>(o.spike_val)[g] = m.sv;
-        reinterpret_cast<uint16_t*>(o.spike_idx)[g] = (uint16_t)m.si;
-    }
-}
-
-// ---- decoder core: this lane's 8 elements of one packed record -> 8 fp32 values ---------------------------------
-template <bool SR> __device__ __forceinline__ GroupMeta load_meta(const Sections& p, uint64_t g, bool meta_fp32) {
-    GroupMeta m;
-    if (meta_fp32) {
-        m.s = reinterpret_cast<const float*>(p.scale)[g];
-        m.lo = reinterpret_cast<const float*>(p.zero)[g];
-    } else {
-        m.s = u2f((uint32_t) reinterpret_cast<const uint16_t*>(p.scale)[g] << 16);
-        m.lo = u2f((uint32_t) reinterpret_cast<const uint16_t*>(p.zero)[g] << 16);
-    }
-    if (SR) {
-        m.sv = reinterpret_cast<const uint32_t*>(p.spike_val)[g];
-        m.si = reinterpret_cast<const uint16_t*>(p.spike_idx)[g];
-    } else {
-        m.sv = 0;
-        m.si = 0;
-    }
-    return m;
-}
-
-// v[j] = fma(code_j, scale, lo); spike positions get the stored float (Section 3.3: restored in place).
-// spike_mask: bit j set where element j of this lane is a restored spike.
-template <int BITS, bool SR>
-__device__ __forceinline__ void dequant8(const Sections& p, uint64_t L, uint32_t lig, const GroupMeta& m, float (&v)[8],
-                                         uint32_t& spike_mask, uint32_t (&spike_bits)[2]) {
-    using P = Planes<BITS>;
-    float q[8];
+    constexpr int U = EPL / 8;  // 8-element units
     if (P::w8) {
-        const uint2 c = *reinterpret_cast<const uint2*>(p.plane8 + 8 * L);
+#pragma unroll
+        for (int u = 0; u < U; u += 2) {
+            uint8_t* at = base + (r.plane8 + (uint32_t)EPL * L + 8u * u);
+            if (U >= 2)
+                *reinterpret_cast<uint4*>(at) = make_uint4(c[2 * u], c[2 * u + 1], c[2 * u + 2], c[2 * u + 3]);
+            else
+                *reinterpret_cast<uint2*>(at) = make_uint2(c[0], c[1]);
+        }
+    }
+    if (P::w4) {
+        uint32_t q[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) q[u] = pack_plane4<P::sh4, BITS>(c[2 * u], c[2 * u + 1]);
+        uint8_t* at = base + (r.plane4 + (uint32_t)(EPL / 2) * L);
+        if (U == 4) *reinterpret_cast<uint4*>(at) = make_uint4(q[0], q[1], q[2], q[3]);
+        if (U == 2) *reinterpret_cast<uint2*>(at) = make_uint2(q[0], q[1]);
+        if (U == 1) *reinterpret_cast<uint32_t*>(at) = q[0];
+    }
+    if (P::w2) {
+        uint32_t q[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) q[u] = pack_plane2<P::sh2, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFFFu;
+        uint8_t* at = base + (r.plane2 + (uint32_t)(EPL / 4) * L);
+        if (U == 4) *reinterpret_cast<uint2*>(at) = make_uint2(q[0] | (q[1] << 16), q[2] | (q[3] << 16));
+        if (U == 2) *reinterpret_cast<uint32_t*>(at) = q[0] | (q[1] << 16);
+        if (U == 1) *reinterpret_cast<uint16_t*>(at) = (uint16_t)q[0];
+    }
+    if (P::w1) {
+        uint32_t q = 0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) q |= (pack_plane1<P::sh1, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFu) << (8 * u);
+        uint8_t* at = base + (r.plane1 + (uint32_t)(EPL / 8) * L);
+        if (U == 4) *reinterpret_cast<uint32_t*>(at) = q;
+        if (U == 2) *reinterpret_cast<uint16_t*>(at) = (uint16_t)q;
+        if (U == 1) *at = (uint8_t)q;
+    }
+}
+
+template <bool SR> __device__ __forceinline__ void store_meta(uint8_t* base, const Rec& r, uint32_t g, const GroupMeta& m, bool meta_fp32) {
+    if (meta_fp32) {
+        *reinterpret_cast<float*>(base + (r.scale + 4u * g)) = m.s;
+        *reinterpret_cast<float*>(base + (r.zero + 4u * g)) = m.lo;
+    } else {
+        *reinterpret_cast<uint16_t*>(base + (r.scale + 2u * g)) = (uint16_t)(f2u(m.s) >> 16);
+        *reinterpret_cast<uint16_t*>(base + (r.zero + 2u * g)) = (uint16_t)(f2u(m.lo) >> 16);
+    }
+    if (SR) {
+        *reinterpret_cast<uint32_t*>(base + (r.spike_val + 4u * g)) = m.sv;
+        *reinterpret_cast<uint16_t*>(base + (r.spike_idx + 2u * g)) = (uint16_t)m.si;
+    }
+}
+
+// ---- decoder core ------------------------------------------------------------------------------------------------
+// Address = uniform base + 32-bit lane offset.  Keeping the offset opaque at the point of use stops the compiler
+// from widening it to 64 bits outside the peer loop, so every load keeps the scalar-base addressing form and
+// needs no address arithmetic of its own.
+__device__ __forceinline__ const uint8_t* at32(const uint8_t* __restrict__ base, uint32_t off) {
+    asm volatile("" : "+v"(off));
+    return base + off;
+}
+
+// Plane pieces of one lane: EPL elements.
+template <int EPL> struct RawPlanes {
+    uint32_t p8[EPL / 4], p4[EPL / 8], p2[(EPL + 15) / 16], p1;
+};
+
+template <int BITS, int EPL> __device__ __forceinline__ RawPlanes<EPL> load_planes(const uint8_t* __restrict__ base, const Rec& r, uint32_t L) {
+    using P = Planes<BITS>;
+    RawPlanes<EPL> o = {};
+    if (P::w8) {
+        const uint8_t* at = at32(base, r.plane8 + (uint32_t)EPL * L);
+        if (EPL == 8) {
+            const uint2 v = *reinterpret_cast<const uint2*>(at);
+            o.p8[0] = v.x;
+            o.p8[1] = v.y;
+        } else {
+#pragma unroll
+            for (int i = 0; i < EPL / 16; ++i) {
+                const uint4 v = reinterpret_cast<const uint4*>(at)[i];
+                o.p8[4 * i] = v.x;
+                o.p8[4 * i + 1] = v.y;
+                o.p8[4 * i + 2] = v.z;
+                o.p8[4 * i + 3] = v.w;
+            }
+        }
+    }
+    if (P::w4) {
+        const uint8_t* at = at32(base, r.plane4 + (uint32_t)(EPL / 2) * L);
+        if (EPL == 8) o.p4[0] = *reinterpret_cast<const uint32_t*>(at);
+        if (EPL == 16) {
+            const uint2 v = *reinterpret_cast<const uint2*>(at);
+            o.p4[0] = v.x;
+            o.p4[EPL / 8 - 1] = v.y;
+        }
+        if (EPL == 32) {
+            const uint4 v = *reinterpret_cast<const uint4*>(at);
+            o.p4[0] = v.x;
+            o.p4[1 % (EPL / 8)] = v.y;
+            o.p4[2 % (EPL / 8)] = v.z;
+            o.p4[3 % (EPL / 8)] = v.w;
+        }
+    }
+    if (P::w2) {
+        const uint8_t* at = at32(base, r.plane2 + (uint32_t)(EPL / 4) * L);
+        if (EPL == 8) o.p2[0] = *reinterpret_cast<const uint16_t*>(at);
+        if (EPL == 16) o.p2[0] = *reinterpret_cast<const uint32_t*>(at);
+        if (EPL == 32) {
+            const uint2 v = *reinterpret_cast<const uint2*>(at);
+            o.p2[0] = v.x;
+            o.p2[(EPL + 15) / 16 - 1] = v.y;
+        }
+    }
+    if (P::w1) {
+        const uint8_t* at = at32(base, r.plane1 + (uint32_t)(EPL / 8) * L);
+        if (EPL == 8) o.p1 = *at;
+        if (EPL == 16) o.p1 = *reinterpret_cast<const uint16_t*>(at);
+        if (EPL == 32) o.p1 = *reinterpret_cast<const uint32_t*>(at);
+    }
+    return o;
+}
+
+// fp32 code values of unit u (8 elements) of the lane.
+template <int BITS, int EPL> __device__ __forceinline__ void unit_codes(const RawPlanes<EPL>& r, int u, float (&q)[8]) {
+    using P = Planes<BITS>;
+    if (P::w8) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-            q[j] = (float)((c.x >> (8 * j)) & 0xFFu);
-            q[j + 4] = (float)((c.y >> (8 * j)) & 0xFFu);
+            q[j] = (float)((r.p8[2 * u] >> (8 * j)) & 0xFFu);
+            q[j + 4] = (float)((r.p8[2 * u + 1] >> (8 * j)) & 0xFFu);
         }
     } else {
-        uint32_t p4 = 0, p2 = 0, p1 = 0, ev, od;
-        if (P::w4) p4 = *reinterpret_cast<const uint32_t*>(p.plane4 + 4 * L);
-        if (P::w2) p2 = *reinterpret_cast<const uint16_t*>(p.plane2 + 2 * L);
-        if (P::w1) p1 = *(p.plane1 + L);
+        uint32_t ev, od;
+        const uint32_t p4 = P::w4 ? r.p4[u] : 0u;
+        const uint32_t p2 = P::w2 ? ((r.p2[u >> 1] >> (16 * (u & 1))) & 0xFFFFu) : 0u;
+        const uint32_t p1 = P::w1 ? ((r.p1 >> (8 * u)) & 0xFFu) : 0u;
         codes_even_odd<BITS>(p4, p2, p1, ev, od);
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -227,101 +349,203 @@ __device__ __forceinline__ void dequant8(const Sections& p, uint64_t L, uint32_t
             q[2 * i + 1] = (float)((od >> (8 * i)) & 0xFFu);
         }
     }
+}
+
+// --- 8 elements per lane, metadata fetched by quads (used where the values are needed in registers) -----------
+// Everything a lane needs to read its 8 elements out of any record of one layout: byte offsets of the one
+// metadata item it fetches for its quad (lane & 3: scale, zero, spike values, spike indices), computed once and
+// reused for every peer.
+struct MetaOffsets {
+    uint32_t at, shift;
+    uint32_t to_f32;  // left shift that turns a stored scale/zero into fp32 bits: 16 for bf16, 0 for fp32
+};
+
+template <int LPG, bool SR> __device__ __forceinline__ MetaOffsets meta_offsets(const Rec& r, uint32_t L, bool meta_fp32) {
+    const uint32_t g = L / LPG, item = L & 3u;
+    const uint32_t msz = meta_fp32 ? 4u : 2u;
+    uint32_t at = r.scale + msz * g;               // item 0, and every item when there are no spikes
+    if (item == 1u) at = r.zero + msz * g;
+    if (SR && item == 2u) at = r.spike_val + 4u * g;
+    if (SR && item == 3u) at = r.spike_idx + 2u * g;
+    MetaOffsets o;
+    o.at = at & ~3u;                                 // aligned dword that holds the item
+    o.shift = (at & 2u) * 8u;
+    o.to_f32 = meta_fp32 ? 0u : 16u;
+    return o;
+}
+
+template <bool SR> __device__ __forceinline__ GroupMeta spread_meta(uint32_t raw, const MetaOffsets& o) {
+    const uint32_t val = raw >> o.shift;
+    GroupMeta m;
+    const uint32_t sb = quad_bcast<0>(val), zb = quad_bcast<1>(val);
+    m.s = u2f(sb << o.to_f32);
+    m.lo = u2f(zb << o.to_f32);
+    m.sv = SR ? quad_bcast<2>(val) : 0u;
+    m.si = SR ? (quad_bcast<3>(val) & 0xFFFFu) : 0u;
+    return m;
+}
+
+// v[j] = fma(code_j, scale, lo); spike positions get the stored float (Section 3.3: restored in place).
+template <int BITS, bool SR>
+__device__ __forceinline__ void dequant8(const RawPlanes<8>& r, const GroupMeta& m, uint32_t lig, float (&v)[8]) {
+    float q[8];
+    unit_codes<BITS, 8>(r, 0, q);
 #pragma unroll
     for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(q[j], m.s, m.lo);
-    spike_mask = 0;
     if (SR) {
-        const uint32_t rel0 = (m.si & 0xFFu) - lig * 8u, rel1 = (m.si >> 8) - lig * 8u;
-        const float f0 = u2f(m.sv << 16), f1 = u2f(m.sv & 0xFFFF0000u);
-        spike_bits[0] = m.sv & 0xFFFFu;
-        spike_bits[1] = m.sv >> 16;
+        // One select per element serves both spikes: a lane that owns only one of them (the common case)
+        // substitutes that one; lanes owning both take a second round, skipped when no lane of the wave does.
+        const uint32_t relmin = (m.si & 0xFFu) - lig * 8u, relmax = (m.si >> 8) - lig * 8u;
+        const float fmin_ = u2f(m.sv << 16), fmax_ = u2f(m.sv & 0xFFFF0000u);
+        const bool own_min = relmin < 8u;
+        const uint32_t rel = own_min ? relmin : relmax;
+        const float val = own_min ? fmin_ : fmax_;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            v[j] = (rel0 == (uint32_t)j) ? f0 : v[j];
-            v[j] = (rel1 == (uint32_t)j) ? f1 : v[j];
+        for (int j = 0; j < 8; ++j) v[j] = (rel == (uint32_t)j) ? val : v[j];
+        const uint32_t rel2 = (own_min && relmax < 8u) ? relmax : 0xFFu;
+        if (__builtin_amdgcn_ballot_w64(rel2 != 0xFFu) != 0) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = (rel2 == (uint32_t)j) ? fmax_ : v[j];
         }
-        spike_mask = (rel0 < 8u ? (1u << rel0) : 0u) | (rel1 < 8u ? (0x100u << rel1) : 0u);
     }
 }
 
 // ---- kernels -------------------------------------------------------------------------------------------------------
 constexpr int kBlock = 256;
+constexpr int kEplStream = 32;  // elements per lane in the kernels that stream a tensor once (64 bytes of bf16)
 
-template <int BITS, int LPG, bool SR>
-__global__ __launch_bounds__(kBlock) void k_quantize_pack(const uint4* __restrict__ x, uint64_t n_lanes, Sections out,
-                                                          uint32_t meta_fp32) {
-    const uint64_t L = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+template <int BITS, int EPL, int LPG, bool SR>
+__global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restrict__ x, uint32_t n_lanes, uint8_t* __restrict__ out,
+                                                            Rec rec, uint32_t meta_fp32) {
+    const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
     if (L >= n_lanes) return;  // groups never straddle the end: whole groups leave together
     const uint32_t lig = threadIdx.x & (LPG - 1);
-    const uint4 v = x[L];
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    uint32_t c0, c1;
+    uint32_t w[EPL / 2];
+#pragma unroll
+    for (int i = 0; i < EPL / 8; ++i) {
+        const uint4 v = x[(uint64_t)L * (EPL / 8) + i];
+        w[4 * i] = v.x;
+        w[4 * i + 1] = v.y;
+        w[4 * i + 2] = v.z;
+        w[4 * i + 3] = v.w;
+    }
+    uint32_t c[EPL / 4];
     GroupMeta m;
-    quantize8<BITS, LPG, SR>(w, lig, meta_fp32 != 0, c0, c1, m);
-    store_planes<BITS>(out, L, c0, c1);
-    if (lig == 0) store_meta<SR>(out, L / LPG, m, meta_fp32 != 0);
+    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_fp32 != 0, c, m);
+    store_planes<BITS, EPL>(out, rec, L, c);
+    if (lig == 0) store_meta<SR>(out, rec, L / LPG, m, meta_fp32 != 0);
 }
 
-template <int BITS, int LPG, bool SR>
-__global__ __launch_bounds__(kBlock) void k_unpack_dequant(Sections in, uint64_t n_lanes, void* __restrict__ out,
-                                                           uint32_t out_fp32, uint32_t meta_fp32) {
-    const uint64_t L = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+// Receiver: EPL elements per lane; every lane reads its group's metadata itself; the two spikes of a group are
+// written by the lanes that own their positions, after the lane's own bulk store (same thread, same address:
+// program order holds, and the wait makes the bulk store visible first).
+template <int BITS, int EPL, int LPG, bool SR>
+__global__ __launch_bounds__(kBlock) void k_unpack_dequant_t(const uint8_t* __restrict__ in, Rec rec, uint32_t n_lanes,
+                                                             void* __restrict__ out, uint32_t out_fp32, uint32_t meta_fp32) {
+    const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
     if (L >= n_lanes) return;
     const uint32_t lig = threadIdx.x & (LPG - 1);
-    const GroupMeta m = load_meta<SR>(in, L / LPG, meta_fp32 != 0);
-    float v[8];
-    uint32_t mask, sb[2];
-    dequant8<BITS, SR>(in, L, lig, m, v, mask, sb);
-    if (out_fp32) {
-        float4* o = reinterpret_cast<float4*>(out) + 2 * L;
-        o[0] = make_float4(v[0], v[1], v[2], v[3]);
-        o[1] = make_float4(v[4], v[5], v[6], v[7]);
+    const uint32_t g = L / LPG;
+    const RawPlanes<EPL> r = load_planes<BITS, EPL>(in, rec, L);
+    float s, lo;
+    if (meta_fp32) {
+        s = *reinterpret_cast<const float*>(in + (rec.scale + 4u * g));
+        lo = *reinterpret_cast<const float*>(in + (rec.zero + 4u * g));
     } else {
-        uint32_t h[8];
+        s = u2f((uint32_t) * reinterpret_cast<const uint16_t*>(in + (rec.scale + 2u * g)) << 16);
+        lo = u2f((uint32_t) * reinterpret_cast<const uint16_t*>(in + (rec.zero + 2u * g)) << 16);
+    }
+    uint32_t sv = 0, si = 0;
+    if (SR) {
+        sv = *reinterpret_cast<const uint32_t*>(in + (rec.spike_val + 4u * g));
+        si = *reinterpret_cast<const uint16_t*>(in + (rec.spike_idx + 2u * g));
+    }
+    const uint64_t e0 = (uint64_t)L * EPL;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            h[j] = bf16_rne_bits(f2u(v[j]));
-            if (SR) {  // spikes keep their stored bit pattern
-                h[j] = (mask & (1u << j)) ? sb[0] : h[j];
-                h[j] = (mask & (0x100u << j)) ? sb[1] : h[j];
+    for (int u = 0; u < EPL / 8; ++u) {
+        float q[8], v[8];
+        unit_codes<BITS, EPL>(r, u, q);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(q[j], s, lo);
+        if (out_fp32) {
+            float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + e0) + 2 * u;
+            dst[0] = make_float4(v[0], v[1], v[2], v[3]);
+            dst[1] = make_float4(v[4], v[5], v[6], v[7]);
+        } else {
+            reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(out) + e0)[u] =
+                make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
+        }
+    }
+    if (SR) {
+        const uint32_t relmin = (si & 0xFFu) - lig * (uint32_t)EPL, relmax = (si >> 8) - lig * (uint32_t)EPL;
+        if (relmin < (uint32_t)EPL || relmax < (uint32_t)EPL) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the bulk stores above have been written
+            if (out_fp32) {
+                float* o = reinterpret_cast<float*>(out) + e0;
+                if (relmin < (uint32_t)EPL) o[relmin] = u2f(sv << 16);
+                if (relmax < (uint32_t)EPL) o[relmax] = u2f(sv & 0xFFFF0000u);
+            } else {
+                uint16_t* o = reinterpret_cast<uint16_t*>(out) + e0;
+                if (relmin < (uint32_t)EPL) o[relmin] = (uint16_t)sv;
+                if (relmax < (uint32_t)EPL) o[relmax] = (uint16_t)(sv >> 16);
             }
         }
-        reinterpret_cast<uint4*>(out)[L] =
-            make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
     }
 }
 
 template <int BITS, int LPG, bool SR>
-__global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerArgs peers, int n_peers, uint64_t n_lanes, Sections out,
-                                                           float* __restrict__ sum_out, uint32_t meta_fp32_in,
-                                                           uint32_t meta_fp32_out) {
-    const uint64_t L = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+__global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
+                                                           uint8_t* __restrict__ out, Rec rec_out, float* __restrict__ sum_out,
+                                                           uint32_t meta_fp32_in, uint32_t meta_fp32_out) {
+    const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
     if (L >= n_lanes) return;
     const uint32_t lig = threadIdx.x & (LPG - 1);
-    const uint64_t g = L / LPG;
+    const MetaOffsets mo = meta_offsets<LPG, SR>(rec_in, L, meta_fp32_in != 0);
+    // -0 is the identity of fp32 addition for every value including -0, so the chain below starts exactly at v_0
     float acc[8];
-    for (int p = 0; p < n_peers; ++p) {
-        const Sections& ps = peers.s[p];
-        const GroupMeta m = load_meta<SR>(ps, g, meta_fp32_in != 0);
-        float v[8];
-        uint32_t mask, sb[2];
-        dequant8<BITS, SR>(ps, L, lig, m, v, mask, sb);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = (p == 0) ? v[j] : __fadd_rn(acc[j], v[j]);
+    for (int j = 0; j < 8; ++j) acc[j] = -0.0f;
+    int p = 0;
+    // four peers at a time: all loads first, so their latencies overlap
+    for (; p + 4 <= n_peers; p += 4) {
+        RawPlanes<8> r[4];
+        uint32_t mraw[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            r[i] = load_planes<BITS, 8>(peers.base[p + i], rec_in, L);
+            mraw[i] = *reinterpret_cast<const uint32_t*>(at32(peers.base[p + i], mo.at));
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const GroupMeta m = spread_meta<SR>(mraw[i], mo);
+            float v[8];
+            dequant8<BITS, SR>(r[i], m, lig, v);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j] = __fadd_rn(acc[j], v[j]);
+        }
+    }
+    for (; p < n_peers; ++p) {
+        const RawPlanes<8> r = load_planes<BITS, 8>(peers.base[p], rec_in, L);
+        const uint32_t mraw = *reinterpret_cast<const uint32_t*>(at32(peers.base[p], mo.at));
+        const GroupMeta m = spread_meta<SR>(mraw, mo);
+        float v[8];
+        dequant8<BITS, SR>(r, m, lig, v);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[j] = __fadd_rn(acc[j], v[j]);
     }
     if (sum_out) {
-        float4* o = reinterpret_cast<float4*>(sum_out) + 2 * L;
-        o[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        o[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        float4* dst = reinterpret_cast<float4*>(sum_out) + 2 * (uint64_t)L;
+        dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
     }
     uint32_t w[4];
 #pragma unroll
-    for (int d = 0; d < 4; ++d) w[d] = bf16_rne_bits(f2u(acc[2 * d])) | (bf16_rne_bits(f2u(acc[2 * d + 1])) << 16);
-    uint32_t c0, c1;
+    for (int d = 0; d < 4; ++d) w[d] = pack_bf16(acc[2 * d], acc[2 * d + 1]);
+    uint32_t c[2];
     GroupMeta m;
-    quantize8<BITS, LPG, SR>(w, lig, meta_fp32_out != 0, c0, c1, m);
-    store_planes<BITS>(out, L, c0, c1);
-    if (lig == 0) store_meta<SR>(out, g, m, meta_fp32_out != 0);
+    quantize_lane<BITS, 8, LPG, SR>(w, lig, meta_fp32_out != 0, c, m);
+    store_planes<BITS, 8>(out, rec_out, L, c);
+    if (lig == 0) store_meta<SR>(out, rec_out, L / LPG, m, meta_fp32_out != 0);
 }
 
 // ---- dispatch: stable counting sort of the routed copies by expert, then quantize-and-scatter ------------------------
@@ -439,41 +663,42 @@ __global__ __launch_bounds__(kChunk) void k_dispatch_rank(const int32_t* __restr
     }
 }
 
-// Quantize every token once, store the packed row K times.  Row sections are relative offsets (align 16).
-struct RowLayout {
-    uint32_t plane8, plane4, plane2, plane1, scale, zero, spike_val, spike_idx, row_bytes;
-};
-
-template <int BITS, int LPG, bool SR>
-__global__ __launch_bounds__(kBlock) void k_dispatch_quant(const uint4* __restrict__ x, uint64_t n_lanes, uint32_t lanes_per_row,
-                                                           uint32_t K, const int32_t* __restrict__ dest, uint8_t* __restrict__ send,
-                                                           RowLayout rl, uint32_t meta_fp32) {
-    const uint64_t L = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+// Quantize every token once, store the packed row K times.  `rec` holds the row's section offsets (align 16).
+template <int BITS, int EPL, int LPG, bool SR>
+__global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __restrict__ x, uint32_t n_lanes, uint32_t lanes_per_row,
+                                                             uint32_t K, const int32_t* __restrict__ dest, uint8_t* __restrict__ send,
+                                                             Rec rec, uint32_t row_bytes, uint32_t meta_fp32) {
+    const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
     if (L >= n_lanes) return;
     const uint32_t lig = threadIdx.x & (LPG - 1);
-    const uint64_t t = L / lanes_per_row;
-    const uint32_t r = (uint32_t)(L - t * lanes_per_row);  // lane inside the row
-    const uint4 v = x[L];
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    uint32_t c0, c1;
+    const uint32_t t = L / lanes_per_row;
+    const uint32_t r = L - t * lanes_per_row;  // lane inside the row
+    uint32_t w[EPL / 2];
+#pragma unroll
+    for (int i = 0; i < EPL / 8; ++i) {
+        const uint4 v = x[(uint64_t)L * (EPL / 8) + i];
+        w[4 * i] = v.x;
+        w[4 * i + 1] = v.y;
+        w[4 * i + 2] = v.z;
+        w[4 * i + 3] = v.w;
+    }
+    uint32_t c[EPL / 4];
     GroupMeta m;
-    quantize8<BITS, LPG, SR>(w, lig, meta_fp32 != 0, c0, c1, m);
+    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_fp32 != 0, c, m);
+    const uint32_t g = r / LPG;
     for (uint32_t k = 0; k < K; ++k) {
         const int32_t row = dest[t * K + k];
         if (row < 0) continue;
-        uint8_t* base = send + (uint64_t)row * rl.row_bytes;
-        Sections o;
-        o.plane8 = base + rl.plane8;
-        o.plane4 = base + rl.plane4;
-        o.plane2 = base + rl.plane2;
-        o.plane1 = base + rl.plane1;
-        o.scale = base + rl.scale;
-        o.zero = base + rl.zero;
-        o.spike_val = base + rl.spike_val;
-        o.spike_idx = base + rl.spike_idx;
-        store_planes<BITS>(o, r, c0, c1);
-        if (lig == 0) store_meta<SR>(o, r / LPG, m, meta_fp32 != 0);
+        uint8_t* base = send + (uint64_t)(uint32_t)row * row_bytes;
+        store_planes<BITS, EPL>(base, rec, r, c);
+        if (lig == 0) store_meta<SR>(base, rec, g, m, meta_fp32 != 0);
     }
+}
+
+// Plain streaming copy (16 bytes per lane), used to measure the practical HBM ceiling next to the codec kernels.
+__global__ __launch_bounds__(kBlock) void k_stream_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, uint64_t n16) {
+    const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
 }
 
 // ---- host side ---------------------------------------------------------------------------------------------------------
@@ -485,28 +710,28 @@ static bool fmt_supported(const fcv2_fmt_t* f) {
 
 static inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
-static Sections sections_of(const void* base, const fcv2_layout_t& l) {
-    uint8_t* b = (uint8_t*)base;
-    Sections s;
-    s.plane8 = l.off_plane8 == FCV2_ABSENT ? nullptr : b + l.off_plane8;
-    s.plane4 = l.off_plane4 == FCV2_ABSENT ? nullptr : b + l.off_plane4;
-    s.plane2 = l.off_plane2 == FCV2_ABSENT ? nullptr : b + l.off_plane2;
-    s.plane1 = l.off_plane1 == FCV2_ABSENT ? nullptr : b + l.off_plane1;
-    s.scale = b + l.off_scale;
-    s.zero = b + l.off_zero;
-    s.spike_val = l.off_spike_val == FCV2_ABSENT ? nullptr : b + l.off_spike_val;
-    s.spike_idx = l.off_spike_idx == FCV2_ABSENT ? nullptr : b + l.off_spike_idx;
-    return s;
+static Rec rec_of(const fcv2_layout_t& l) {
+    auto rel = [](uint64_t o) { return o == FCV2_ABSENT ? 0u : (uint32_t)o; };
+    Rec r;
+    r.plane8 = rel(l.off_plane8);
+    r.plane4 = rel(l.off_plane4);
+    r.plane2 = rel(l.off_plane2);
+    r.plane1 = rel(l.off_plane1);
+    r.scale = rel(l.off_scale);
+    r.zero = rel(l.off_zero);
+    r.spike_val = rel(l.off_spike_val);
+    r.spike_idx = rel(l.off_spike_idx);
+    return r;
 }
 
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
-// Calls F<BITS, LPG, SR>::run(args...) for the runtime format.
+// Calls F<BITS, G, SR>::run(args...) for the runtime format.
 template <template <int, int, bool> class F, typename... A> static int by_format(const fcv2_fmt_t* f, A&&... a) {
     const bool sr = (f->flags & FCV2_F_SPIKE) != 0;
 #define FCV2_CASE_G(B, G)                                                          \
     case G:                                                                        \
-        return sr ? F<B, G / 8, true>::run(a...) : F<B, G / 8, false>::run(a...);
+        return sr ? F<B, G, true>::run(a...) : F<B, G, false>::run(a...);
 #define FCV2_CASE_B(B)                 \
     case B:                            \
         switch (f->group) {            \
@@ -531,35 +756,43 @@ template <template <int, int, bool> class F, typename... A> static int by_format
 }
 
 static inline int launch_status() { return hipGetLastError() == hipSuccess ? FCV2_OK : FCV2_ERR_LAUNCH; }
-static inline unsigned grid_for(uint64_t n_lanes) { return (unsigned)((n_lanes + kBlock - 1) / kBlock); }
 
-template <int BITS, int LPG, bool SR> struct LaunchQuantize {
-    static int run(const void* x, uint64_t n_lanes, const Sections& out, uint32_t meta_fp32, hipStream_t st) {
-        hipLaunchKernelGGL((k_quantize_pack<BITS, LPG, SR>), dim3(grid_for(n_lanes)), dim3(kBlock), 0, st, (const uint4*)x,
-                           n_lanes, out, meta_fp32);
+static inline unsigned grid_lanes(uint32_t n_lanes) { return (unsigned)((n_lanes + kBlock - 1) / kBlock); }
+
+template <int BITS, int G, bool SR> struct LaunchQuantize {
+    static int run(const void* x, uint64_t n, void* out, const Rec& rec, uint32_t meta_fp32, hipStream_t st) {
+        constexpr int EPL = kEplStream;
+        const uint32_t n_lanes = (uint32_t)(n / EPL);
+        hipLaunchKernelGGL((k_quantize_pack_t<BITS, EPL, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
+                           (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_fp32);
         return launch_status();
     }
 };
-template <int BITS, int LPG, bool SR> struct LaunchUnpack {
-    static int run(const Sections& in, uint64_t n_lanes, void* out, uint32_t out_fp32, uint32_t meta_fp32, hipStream_t st) {
-        hipLaunchKernelGGL((k_unpack_dequant<BITS, LPG, SR>), dim3(grid_for(n_lanes)), dim3(kBlock), 0, st, in, n_lanes, out,
-                           out_fp32, meta_fp32);
+template <int BITS, int G, bool SR> struct LaunchUnpack {
+    static int run(const void* in, const Rec& rec, uint64_t n, void* out, uint32_t out_fp32, uint32_t meta_fp32, hipStream_t st) {
+        constexpr int EPL = kEplStream;
+        const uint32_t n_lanes = (uint32_t)(n / EPL);
+        hipLaunchKernelGGL((k_unpack_dequant_t<BITS, EPL, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
+                           (const uint8_t*)in, rec, n_lanes, out, out_fp32, meta_fp32);
         return launch_status();
     }
 };
-template <int BITS, int LPG, bool SR> struct LaunchReduce {
-    static int run(const PeerArgs& peers, int n_peers, uint64_t n_lanes, const Sections& out, float* sum_out, uint32_t mf_in,
-                   uint32_t mf_out, hipStream_t st) {
-        hipLaunchKernelGGL((k_reduce_requant<BITS, LPG, SR>), dim3(grid_for(n_lanes)), dim3(kBlock), 0, st, peers, n_peers,
-                           n_lanes, out, sum_out, mf_in, mf_out);
+template <int BITS, int G, bool SR> struct LaunchReduce {
+    static int run(const PeerPtrs& peers, int n_peers, uint64_t n, const Rec& rec_in, void* out, const Rec& rec_out,
+                   float* sum_out, uint32_t mf_in, uint32_t mf_out, hipStream_t st) {
+        const uint32_t n_lanes = (uint32_t)(n / 8);
+        hipLaunchKernelGGL((k_reduce_requant<BITS, G / 8, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st, peers, n_peers,
+                           n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
         return launch_status();
     }
 };
-template <int BITS, int LPG, bool SR> struct LaunchDispatch {
-    static int run(const void* x, uint64_t n_lanes, uint32_t lanes_per_row, uint32_t K, const int32_t* dest, uint8_t* send,
-                   const RowLayout& rl, uint32_t meta_fp32, hipStream_t st) {
-        hipLaunchKernelGGL((k_dispatch_quant<BITS, LPG, SR>), dim3(grid_for(n_lanes)), dim3(kBlock), 0, st, (const uint4*)x,
-                           n_lanes, lanes_per_row, K, dest, send, rl, meta_fp32);
+template <int BITS, int G, bool SR> struct LaunchDispatch {
+    static int run(const void* x, uint64_t n, uint32_t H, uint32_t K, const int32_t* dest, uint8_t* send, const Rec& rec,
+                   uint32_t row_bytes, uint32_t meta_fp32, hipStream_t st) {
+        constexpr int EPL = kEplStream;
+        const uint32_t n_lanes = (uint32_t)(n / EPL);
+        hipLaunchKernelGGL((k_dispatch_quant_t<BITS, EPL, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
+                           (const uint4*)x, n_lanes, H / EPL, K, dest, send, rec, row_bytes, meta_fp32);
         return launch_status();
     }
 };
@@ -631,14 +864,18 @@ int fcv2_get_layout(uint64_t n, const fcv2_fmt_t* fmt, uint32_t align, fcv2_layo
     return FCV2_OK;
 }
 
+// Largest tensor the kernels index with 32-bit offsets: 2^31 elements (a 4 GiB bf16 tensor).
+static const uint64_t kMaxElems = 1ull << 31;
+
 int fcv2_quantize_pack(const void* x, uint64_t n, const fcv2_fmt_t* fmt, void* packed, void* stream) {
     if (!x || !packed || !fmt) return FCV2_ERR_INVALID_ARG;
     fcv2_layout_t l;
     int rc = fcv2_get_layout(n, fmt, FCV2_TENSOR_ALIGN, &l);
     if (rc != FCV2_OK) return rc;
+    if (n > kMaxElems) return FCV2_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(packed)) return FCV2_ERR_ALIGN;
-    return by_format<LaunchQuantize>(fmt, x, n / 8, sections_of(packed, l), (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0),
-                                     (hipStream_t)stream);
+    return by_format<LaunchQuantize>(fmt, x, n, packed, rec_of(l),
+                                     (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0), (hipStream_t)stream);
 }
 
 int fcv2_unpack_dequant(const void* packed, uint64_t n, const fcv2_fmt_t* fmt, void* out, int out_dtype, void* stream) {
@@ -647,8 +884,9 @@ int fcv2_unpack_dequant(const void* packed, uint64_t n, const fcv2_fmt_t* fmt, v
     fcv2_layout_t l;
     int rc = fcv2_get_layout(n, fmt, FCV2_TENSOR_ALIGN, &l);
     if (rc != FCV2_OK) return rc;
+    if (n > kMaxElems) return FCV2_ERR_UNSUPPORTED;
     if (!aligned16(packed) || !aligned16(out)) return FCV2_ERR_ALIGN;
-    return by_format<LaunchUnpack>(fmt, sections_of(packed, l), n / 8, out, (uint32_t)(out_dtype == FCV2_DT_FP32),
+    return by_format<LaunchUnpack>(fmt, packed, rec_of(l), n, out, (uint32_t)(out_dtype == FCV2_DT_FP32),
                                    (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0), (hipStream_t)stream);
 }
 
@@ -661,18 +899,19 @@ int fcv2_reduce_requant(const void* const* peers, int n_peers, uint64_t n, const
     if (rc != FCV2_OK) return rc;
     rc = fcv2_get_layout(n, fmt_out, FCV2_TENSOR_ALIGN, &lout);
     if (rc != FCV2_OK) return rc;
+    if (n > kMaxElems) return FCV2_ERR_UNSUPPORTED;
     if (fmt_in->bits != fmt_out->bits || fmt_in->group != fmt_out->group ||
         ((fmt_in->flags ^ fmt_out->flags) & FCV2_F_SPIKE) != 0)
         return FCV2_ERR_UNSUPPORTED;
     if (!aligned16(packed_out) || (sum_out && !aligned16(sum_out))) return FCV2_ERR_ALIGN;
-    PeerArgs pa;
+    PeerPtrs pp;
     for (int p = 0; p < FCV2_MAX_PEERS; ++p) {
         const void* ptr = peers[p < n_peers ? p : 0];
         if (!ptr) return FCV2_ERR_INVALID_ARG;
         if (!aligned16(ptr)) return FCV2_ERR_ALIGN;
-        pa.s[p] = sections_of(ptr, lin);
+        pp.base[p] = (const uint8_t*)ptr;
     }
-    return by_format<LaunchReduce>(fmt_in, pa, n_peers, n / 8, sections_of(packed_out, lout), sum_out,
+    return by_format<LaunchReduce>(fmt_in, pp, n_peers, n, rec_of(lin), packed_out, rec_of(lout), sum_out,
                                    (uint32_t)((fmt_in->flags & FCV2_F_META_FP32) != 0),
                                    (uint32_t)((fmt_out->flags & FCV2_F_META_FP32) != 0), (hipStream_t)stream);
 }
@@ -694,6 +933,7 @@ int fcv2_dispatch_quant(const void* x, const int32_t* ids, uint32_t T, uint32_t 
     fcv2_layout_t l;
     rc = fcv2_get_layout(H, fmt, FCV2_ROW_ALIGN, &l);
     if (rc != FCV2_OK) return rc;
+    if ((uint64_t)T * H > kMaxElems) return FCV2_ERR_UNSUPPORTED;
     if (ws_bytes < need) return FCV2_ERR_WORKSPACE;
     if (!aligned16(x) || !aligned16(send) || !aligned16(ws) || ((uintptr_t)ids & 3u) || ((uintptr_t)expert_offsets & 3u) ||
         ((uintptr_t)row_src & 3u))
@@ -709,19 +949,17 @@ int fcv2_dispatch_quant(const void* x, const int32_t* ids, uint32_t T, uint32_t 
     hipLaunchKernelGGL(k_dispatch_rank, dim3(w.n_chunks), dim3(kChunk), (kChunk / 64) * E * 4, st, ids, w.n_slots, E, hist,
                        expert_offsets, dest, row_src);
     if (launch_status() != FCV2_OK) return FCV2_ERR_LAUNCH;
-    RowLayout rl;
-    auto rel = [](uint64_t o) { return o == FCV2_ABSENT ? 0u : (uint32_t)o; };
-    rl.plane8 = rel(l.off_plane8);
-    rl.plane4 = rel(l.off_plane4);
-    rl.plane2 = rel(l.off_plane2);
-    rl.plane1 = rel(l.off_plane1);
-    rl.scale = rel(l.off_scale);
-    rl.zero = rel(l.off_zero);
-    rl.spike_val = rel(l.off_spike_val);
-    rl.spike_idx = rel(l.off_spike_idx);
-    rl.row_bytes = (uint32_t)l.total_bytes;
-    return by_format<LaunchDispatch>(fmt, x, (uint64_t)T * H / 8, H / 8, K, (const int32_t*)dest, (uint8_t*)send, rl,
-                                     (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0), st);
+    return by_format<LaunchDispatch>(fmt, x, (uint64_t)T * H, H, K, (const int32_t*)dest, (uint8_t*)send,
+                                     rec_of(l), (uint32_t)l.total_bytes, (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0), st);
+}
+
+int fcv2_stream_copy(const void* src, void* dst, uint64_t bytes, void* stream) {
+    if (!src || !dst || bytes == 0 || bytes % 16 != 0) return FCV2_ERR_INVALID_ARG;
+    if (!aligned16(src) || !aligned16(dst)) return FCV2_ERR_ALIGN;
+    const uint64_t n16 = bytes / 16;
+    hipLaunchKernelGGL(k_stream_copy, dim3((unsigned)((n16 + kBlock - 1) / kBlock)), dim3(kBlock), 0, (hipStream_t)stream,
+                       (const uint4*)src, (uint4*)dst, n16);
+    return launch_status();
 }
 
 }  // extern "C"
