@@ -132,4 +132,35 @@ template <int BITS> FCV2_HD void codes_even_odd(uint32_t p4, uint32_t p2, uint32
     FCV2_KEEP(od);
 }
 
+// Codes of 8 elements as four "pair" registers: Q[k] holds element k in bits 0..15 and element k+4 in bits
+// 16..31, each zero-extended.  Read as an fp16 denormal, a 16-bit integer q is exactly q * 2^-24, which lets a
+// mixed-precision FMA consume the code without a separate integer-to-float conversion.
+// p8lo/p8hi: the 8 plane-8 bytes; p4 / p2 / p1: the 32 / 16 / 8 bits of the other planes.
+template <int BITS> FCV2_HD void codes_pairs(uint32_t p8lo, uint32_t p8hi, uint32_t p4, uint32_t p2, uint32_t p1, uint32_t (&Q)[4]) {
+    using P = Planes<BITS>;
+    if (P::w8) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        Q[0] = __builtin_amdgcn_perm(p8hi, p8lo, 0x0C040C00u);
+        Q[1] = __builtin_amdgcn_perm(p8hi, p8lo, 0x0C050C01u);
+        Q[2] = __builtin_amdgcn_perm(p8hi, p8lo, 0x0C060C02u);
+        Q[3] = __builtin_amdgcn_perm(p8hi, p8lo, 0x0C070C03u);
+#else
+        for (int k = 0; k < 4; ++k) Q[k] = ((p8lo >> (8 * k)) & 0xFFu) | (((p8hi >> (8 * k)) & 0xFFu) << 16);
+#endif
+        return;
+    }
+    // element k of the low half and element k+4 of the high half sit at the same offset inside their halves
+    const uint32_t A2 = P::w2 ? ((p2 << 8) | p2) : 0u;   // bits 0..7: fields 0..3, bits 16..23: fields 4..7
+    const uint32_t A1 = P::w1 ? ((p1 << 12) | p1) : 0u;  // bits 0..3: fields 0..3, bits 16..19: fields 4..7
+#define FCV2_SHIFTED(x, amount) ((amount) >= 0 ? ((x) >> ((amount) >= 0 ? (amount) : 0)) : ((x) << ((amount) < 0 ? -(amount) : 0)))
+    for (int k = 0; k < 4; ++k) {
+        uint32_t q = 0;
+        if (P::w4) q |= FCV2_SHIFTED(p4, 4 * k - P::sh4) & (0x000F000Fu << P::sh4);
+        if (P::w2) q |= FCV2_SHIFTED(A2, 2 * k - P::sh2) & (0x00030003u << P::sh2);
+        if (P::w1) q |= FCV2_SHIFTED(A1, k - P::sh1) & (0x00010001u << P::sh1);
+        Q[k] = q;
+    }
+#undef FCV2_SHIFTED
+}
+
 }  // namespace fcv2

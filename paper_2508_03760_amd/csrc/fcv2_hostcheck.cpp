@@ -29,6 +29,16 @@ template <int BITS> static void codes_of_planes(uint32_t p4, uint32_t p2, uint32
     }
 }
 
+template <int BITS> static void pairs_of_planes(uint32_t p8lo, uint32_t p8hi, uint32_t p4, uint32_t p2, uint32_t p1, uint8_t* codes) {
+    uint32_t Q[4];
+    codes_pairs<BITS>(p8lo, p8hi, p4, p2, p1, Q);
+    for (int k = 0; k < 4; ++k) {
+        codes[k] = (uint8_t)(Q[k] & 0xFFFFu);
+        codes[k + 4] = (uint8_t)(Q[k] >> 16);
+        if ((Q[k] & 0xFF00FF00u) != 0) codes[k] = 0xEE;  // must be zero-extended
+    }
+}
+
 template <int QMAX> static uint64_t div_mismatches(uint32_t first_bits, uint32_t count) {
     uint64_t bad = 0;
     for (uint32_t i = 0; i < count; ++i) {
@@ -56,6 +66,15 @@ int hc_codes_of_planes(int bits, uint32_t p4, uint32_t p2, uint32_t p1, uint8_t*
     switch (bits) {
 #define C(B) case B: codes_of_planes<B>(p4, p2, p1, codes); return 0;
         C(2) C(3) C(4) C(5) C(6) C(7)
+#undef C
+    }
+    return -1;
+}
+
+int hc_pairs_of_planes(int bits, uint32_t p8lo, uint32_t p8hi, uint32_t p4, uint32_t p2, uint32_t p1, uint8_t* codes) {
+    switch (bits) {
+#define C(B) case B: pairs_of_planes<B>(p8lo, p8hi, p4, p2, p1, codes); return 0;
+        C(2) C(3) C(4) C(5) C(6) C(7) C(8)
 #undef C
     }
     return -1;

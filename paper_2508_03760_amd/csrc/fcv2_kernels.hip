@@ -15,6 +15,7 @@
 // Compile with -ffp-contract=off.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "../../include/fcv2.h"
 #include "fcv2_bits.h"
@@ -45,6 +46,10 @@ template <int CTRL> __device__ __forceinline__ uint32_t dpp(uint32_t v) {
 template <int K> __device__ __forceinline__ uint32_t quad_bcast(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, K * 0x55, 0xF, 0xF, true);
 }
+
+// Views of LDS rows that are written as vectors and patched as scalars (or the other way round).
+typedef uint32_t __attribute__((may_alias)) u32a;
+typedef uint16_t __attribute__((may_alias)) u16a;
 
 __device__ __forceinline__ float u2f(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t f2u(float f) { return __float_as_uint(f); }
@@ -385,166 +390,283 @@ template <bool SR> __device__ __forceinline__ GroupMeta spread_meta(uint32_t raw
     return m;
 }
 
-// v[j] = fma(code_j, scale, lo); spike positions get the stored float (Section 3.3: restored in place).
-template <int BITS, bool SR>
-__device__ __forceinline__ void dequant8(const RawPlanes<8>& r, const GroupMeta& m, uint32_t lig, float (&v)[8]) {
-    float q[8];
-    unit_codes<BITS, 8>(r, 0, q);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(q[j], m.s, m.lo);
-    if (SR) {
-        // One select per element serves both spikes: a lane that owns only one of them (the common case)
-        // substitutes that one; lanes owning both take a second round, skipped when no lane of the wave does.
-        const uint32_t relmin = (m.si & 0xFFu) - lig * 8u, relmax = (m.si >> 8) - lig * 8u;
-        const float fmin_ = u2f(m.sv << 16), fmax_ = u2f(m.sv & 0xFFFF0000u);
-        const bool own_min = relmin < 8u;
-        const uint32_t rel = own_min ? relmin : relmax;
-        const float val = own_min ? fmin_ : fmax_;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = (rel == (uint32_t)j) ? val : v[j];
-        const uint32_t rel2 = (own_min && relmax < 8u) ? relmax : 0xFFu;
-        if (__builtin_amdgcn_ballot_w64(rel2 != 0xFFu) != 0) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = (rel2 == (uint32_t)j) ? fmax_ : v[j];
-        }
-    }
-}
-
 // ---- kernels -------------------------------------------------------------------------------------------------------
 constexpr int kBlock = 256;
+constexpr int kWaves = kBlock / 64;
 constexpr int kEplStream = 32;  // elements per lane in the kernels that stream a tensor once (64 bytes of bf16)
 
-template <int BITS, int EPL, int LPG, bool SR>
-__global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restrict__ x, uint32_t n_lanes, uint8_t* __restrict__ out,
-                                                            Rec rec, uint32_t meta_fp32) {
-    const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
-    if (L >= n_lanes) return;  // groups never straddle the end: whole groups leave together
-    const uint32_t lig = threadIdx.x & (LPG - 1);
-    uint32_t w[EPL / 2];
-#pragma unroll
-    for (int i = 0; i < EPL / 8; ++i) {
-        const uint4 v = x[(uint64_t)L * (EPL / 8) + i];
-        w[4 * i] = v.x;
-        w[4 * i + 1] = v.y;
-        w[4 * i + 2] = v.z;
-        w[4 * i + 3] = v.w;
-    }
-    uint32_t c[EPL / 4];
-    GroupMeta m;
-    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_fp32 != 0, c, m);
-    store_planes<BITS, EPL>(out, rec, L, c);
-    if (lig == 0) store_meta<SR>(out, rec, L / LPG, m, meta_fp32 != 0);
+// Orders LDS traffic inside one wave: everything written before is visible to reads after (a wave's DS operations
+// execute in order; this only stops the compiler from moving them across).
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Receiver: EPL elements per lane; every lane reads its group's metadata itself; the two spikes of a group are
-// written by the lanes that own their positions, after the lane's own bulk store (same thread, same address:
-// program order holds, and the wait makes the bulk store visible first).
-template <int BITS, int EPL, int LPG, bool SR>
-__global__ __launch_bounds__(kBlock) void k_unpack_dequant_t(const uint8_t* __restrict__ in, Rec rec, uint32_t n_lanes,
-                                                             void* __restrict__ out, uint32_t out_fp32, uint32_t meta_fp32) {
-    const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
-    if (L >= n_lanes) return;
-    const uint32_t lig = threadIdx.x & (LPG - 1);
-    const uint32_t g = L / LPG;
-    const RawPlanes<EPL> r = load_planes<BITS, EPL>(in, rec, L);
-    float s, lo;
-    if (meta_fp32) {
-        s = *reinterpret_cast<const float*>(in + (rec.scale + 4u * g));
-        lo = *reinterpret_cast<const float*>(in + (rec.zero + 4u * g));
-    } else {
-        s = u2f((uint32_t) * reinterpret_cast<const uint16_t*>(in + (rec.scale + 2u * g)) << 16);
-        lo = u2f((uint32_t) * reinterpret_cast<const uint16_t*>(in + (rec.zero + 2u * g)) << 16);
-    }
-    uint32_t sv = 0, si = 0;
-    if (SR) {
-        sv = *reinterpret_cast<const uint32_t*>(in + (rec.spike_val + 4u * g));
-        si = *reinterpret_cast<const uint16_t*>(in + (rec.spike_idx + 2u * g));
-    }
-    const uint64_t e0 = (uint64_t)L * EPL;
+// A wave's tile of 64 x 32 consecutive bf16 (4 KiB) is fetched with fully coalesced 16-byte loads (piece P = k*64 + lane)
+// and turned, through LDS, into 32 consecutive elements per lane.  Rows of 64 bytes are padded to 80 so that the
+// 16-byte reads of 16 neighbouring lanes fall into different banks.
+constexpr int kRowU4 = 5;  // uint4 per lane row: 4 of data + 1 of padding
+
+struct TileIn {
+    uint4 piece[4];
+};
+
+__device__ __forceinline__ TileIn tile_load(const uint4* __restrict__ x, uint64_t tile_piece0, uint32_t lane, uint32_t pieces_left) {
+    TileIn t;
 #pragma unroll
-    for (int u = 0; u < EPL / 8; ++u) {
-        float q[8], v[8];
-        unit_codes<BITS, EPL>(r, u, q);
+    for (int k = 0; k < 4; ++k) {
+        // pieces past the end re-read the last valid one: no branch, so the loads stay in one straight run and
+        // the waits on them can be counted exactly (lanes that own such pieces never use them)
+        const uint32_t P = min(k * 64 + lane, pieces_left - 1u);
+        t.piece[k] = x[tile_piece0 + P];
+    }
+    return t;
+}
+
+__device__ __forceinline__ void tile_transpose(const TileIn& t, uint4* wave_lds, uint32_t lane, uint32_t (&w)[16]) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(q[j], s, lo);
-        if (out_fp32) {
-            float4* dst = reinterpret_cast<float4*>(reinterpret_cast<float*>(out) + e0) + 2 * u;
-            dst[0] = make_float4(v[0], v[1], v[2], v[3]);
-            dst[1] = make_float4(v[4], v[5], v[6], v[7]);
-        } else {
-            reinterpret_cast<uint4*>(reinterpret_cast<uint16_t*>(out) + e0)[u] =
-                make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t P = k * 64 + lane;
+        wave_lds[(P >> 2) * kRowU4 + (P & 3)] = t.piece[k];
+    }
+    wave_lds_sync();
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const uint4 v = wave_lds[lane * kRowU4 + k];
+        w[4 * k] = v.x;
+        w[4 * k + 1] = v.y;
+        w[4 * k + 2] = v.z;
+        w[4 * k + 3] = v.w;
+    }
+    wave_lds_sync();  // the next tile's writes must not overtake these reads
+}
+
+// Sender: persistent waves walk over the tiles; the next tile's loads are in flight while the current one is
+// quantized, so memory and arithmetic overlap inside every wave.
+template <int BITS, int LPG, bool SR>
+__global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restrict__ x, uint32_t n_lanes, uint8_t* __restrict__ out,
+                                                            Rec rec, uint32_t meta_fp32) {
+    constexpr int EPL = kEplStream;
+    __shared__ uint4 lds[kWaves][64 * kRowU4];
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));  // uniform: tiles are per wave
+    const uint32_t lig = lane & (LPG - 1);
+    const uint32_t n_tiles = (n_lanes + 63) / 64;
+    const uint32_t stride = gridDim.x * kWaves;
+    uint32_t tile = blockIdx.x * kWaves + wave;
+    if (tile >= n_tiles) return;
+    const uint32_t n_pieces = n_lanes * 4;
+    auto process = [&](const TileIn& t, uint32_t tl) {
+        uint32_t w[16];
+        tile_transpose(t, lds[wave], lane, w);
+        const uint32_t L = tl * 64 + lane;
+        if (L < n_lanes) {  // groups never straddle the end: whole groups are in or out together
+            uint32_t c[EPL / 4];
+            GroupMeta m;
+            quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_fp32 != 0, c, m);
+            store_planes<BITS, EPL>(out, rec, L, c);
+            if (lig == 0) store_meta<SR>(out, rec, L / LPG, m, meta_fp32 != 0);
         }
+    };
+    // Two tiles are kept in flight per wave (two register sets, ping-pong, so loaded data is never moved); the
+    // refill of a set is issued right after the tile that used it has been stored.  Loads are unconditional
+    // (past the end they re-read the last tile): conditional ones would force full waits.
+    const uint32_t last = n_tiles - 1;
+    TileIn a = tile_load(x, (uint64_t)tile * 256, lane, n_pieces - tile * 256);
+    uint32_t t1 = min(tile + stride, last);
+    TileIn b = tile_load(x, (uint64_t)t1 * 256, lane, n_pieces - t1 * 256);
+    while (true) {
+        process(a, tile);
+        uint32_t t2 = min(tile + 2 * stride, last);
+        a = tile_load(x, (uint64_t)t2 * 256, lane, n_pieces - t2 * 256);
+        tile += stride;
+        if (tile >= n_tiles) break;
+        process(b, tile);
+        t2 = min(tile + 2 * stride, last);
+        b = tile_load(x, (uint64_t)t2 * 256, lane, n_pieces - t2 * 256);
+        tile += stride;
+        if (tile >= n_tiles) break;
     }
-    if (SR) {
-        const uint32_t relmin = (si & 0xFFu) - lig * (uint32_t)EPL, relmax = (si >> 8) - lig * (uint32_t)EPL;
-        if (relmin < (uint32_t)EPL || relmax < (uint32_t)EPL) {
-            __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the bulk stores above have been written
-            if (out_fp32) {
-                float* o = reinterpret_cast<float*>(out) + e0;
-                if (relmin < (uint32_t)EPL) o[relmin] = u2f(sv << 16);
-                if (relmax < (uint32_t)EPL) o[relmax] = u2f(sv & 0xFFFF0000u);
+}
+
+// Receiver: 32 elements per lane; every lane reads its group's metadata itself.  The results go through LDS so that
+// (a) the two spikes of a group are dropped into place by plain indexed LDS writes of the lanes that own their
+// positions (Section 3.3: restored in place) and (b) the global stores are fully coalesced 16-byte pieces.
+template <int BITS, int LPG, bool SR, bool OUT_FP32>
+__global__ __launch_bounds__(kBlock) void k_unpack_dequant_t(const uint8_t* __restrict__ in, Rec rec, uint32_t n_lanes,
+                                                             uint4* __restrict__ out, uint32_t meta_fp32) {
+    constexpr int EPL = kEplStream;
+    constexpr int ROW = OUT_FP32 ? 9 : kRowU4;  // uint4 per lane row incl. one of padding
+    constexpr int NP = OUT_FP32 ? 8 : 4;       // 16-byte pieces per lane
+    __shared__ uint4 lds[kWaves][64 * ROW];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t lig = lane & (LPG - 1);
+    const uint32_t tile = blockIdx.x * kWaves + wave;
+    const uint32_t L = tile * 64 + lane;
+    uint4* row = &lds[wave][lane * ROW];
+    if (L < n_lanes) {
+        const uint32_t g = L / LPG;
+        const RawPlanes<EPL> r = load_planes<BITS, EPL>(in, rec, L);
+        float s, lo;
+        if (meta_fp32) {
+            s = *reinterpret_cast<const float*>(in + (rec.scale + 4u * g));
+            lo = *reinterpret_cast<const float*>(in + (rec.zero + 4u * g));
+        } else {
+            s = u2f((uint32_t) * reinterpret_cast<const uint16_t*>(in + (rec.scale + 2u * g)) << 16);
+            lo = u2f((uint32_t) * reinterpret_cast<const uint16_t*>(in + (rec.zero + 2u * g)) << 16);
+        }
+        uint32_t sv = 0, si = 0;
+        if (SR) {
+            sv = *reinterpret_cast<const uint32_t*>(in + (rec.spike_val + 4u * g));
+            si = *reinterpret_cast<const uint16_t*>(in + (rec.spike_idx + 2u * g));
+        }
+#pragma unroll
+        for (int u = 0; u < EPL / 8; ++u) {
+            float q[8], v[8];
+            unit_codes<BITS, EPL>(r, u, q);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = __fmaf_rn(q[j], s, lo);
+            if (OUT_FP32) {
+                row[2 * u] = make_uint4(f2u(v[0]), f2u(v[1]), f2u(v[2]), f2u(v[3]));
+                row[2 * u + 1] = make_uint4(f2u(v[4]), f2u(v[5]), f2u(v[6]), f2u(v[7]));
             } else {
-                uint16_t* o = reinterpret_cast<uint16_t*>(out) + e0;
+                row[u] = make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
+            }
+        }
+        if (SR) {
+            const uint32_t relmin = (si & 0xFFu) - lig * (uint32_t)EPL, relmax = (si >> 8) - lig * (uint32_t)EPL;
+            if (OUT_FP32) {
+                u32a* o = reinterpret_cast<u32a*>(row);
+                if (relmin < (uint32_t)EPL) o[relmin] = sv << 16;
+                if (relmax < (uint32_t)EPL) o[relmax] = sv & 0xFFFF0000u;
+            } else {
+                u16a* o = reinterpret_cast<u16a*>(row);
                 if (relmin < (uint32_t)EPL) o[relmin] = (uint16_t)sv;
                 if (relmax < (uint32_t)EPL) o[relmax] = (uint16_t)(sv >> 16);
             }
         }
     }
+    wave_lds_sync();
+    const uint32_t n_pieces = n_lanes * NP;
+    const uint32_t piece0 = tile * 64 * NP;
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const uint32_t P = k * 64 + lane;
+        if (piece0 + P < n_pieces) out[(uint64_t)piece0 + P] = lds[wave][(P / NP) * ROW + (P % NP)];
+    }
 }
 
-template <int BITS, int LPG, bool SR>
+// Local reduce step.  EPL = 16 elements per lane (8 for G = 32, so that a group still spans a whole quad).
+//  - codes are unpacked into 16-bit halves and fed to v_fma_mix_f32 as fp16 denormals (q * 2^-24) against the
+//    scale pre-multiplied by 2^24: the product is the same real number q * scale, the FMA rounds once, so the
+//    result is bit-identical to fma(float(q), scale, lo) without a conversion instruction per element;
+//  - the spike positions of every peer are patched through LDS: the (few) lanes that own a spike of this peer
+//    park their values in a private LDS row, overwrite the spike slots with indexed writes and read the row
+//    back -- a dynamic register index done by memory, paid only by the owners.
+template <int BITS, int EPL>
+__device__ __forceinline__ void dequant_mix(const RawPlanes<EPL>& r, float s, float lo, float (&v)[EPL]) {
+    typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+    using P = Planes<BITS>;
+    if (s < 0x1p+100f) {  // always, unless the data spans more than 2^100: then 2^24 * scale could overflow
+        const float s24 = s * 0x1p+24f;
+#pragma unroll
+        for (int u = 0; u < EPL / 8; ++u) {
+            uint32_t Q[4];
+            const uint32_t p4 = P::w4 ? r.p4[u] : 0u;
+            const uint32_t p2 = P::w2 ? ((r.p2[u >> 1] >> (16 * (u & 1))) & 0xFFFFu) : 0u;
+            const uint32_t p1 = P::w1 ? ((r.p1 >> (8 * u)) & 0xFFu) : 0u;
+            codes_pairs<BITS>(P::w8 ? r.p8[2 * u] : 0u, P::w8 ? r.p8[2 * u + 1] : 0u, p4, p2, p1, Q);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const half2v h = __builtin_bit_cast(half2v, Q[k]);
+                v[8 * u + k] = __builtin_fmaf((float)h.x, s24, lo);
+                v[8 * u + k + 4] = __builtin_fmaf((float)h.y, s24, lo);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < EPL / 8; ++u) {
+            float q[8];
+            unit_codes<BITS, EPL>(r, u, q);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[8 * u + j] = __fmaf_rn(q[j], s, lo);
+        }
+    }
+}
+
+template <int EPL> __device__ __forceinline__ void patch_spikes(const GroupMeta& m, uint32_t lig, uint4* row, float (&v)[EPL]) {
+    const uint32_t relmin = (m.si & 0xFFu) - lig * (uint32_t)EPL, relmax = (m.si >> 8) - lig * (uint32_t)EPL;
+    if (relmin < (uint32_t)EPL || relmax < (uint32_t)EPL) {
+#pragma unroll
+        for (int i = 0; i < EPL / 4; ++i) row[i] = make_uint4(f2u(v[4 * i]), f2u(v[4 * i + 1]), f2u(v[4 * i + 2]), f2u(v[4 * i + 3]));
+        u32a* o = reinterpret_cast<u32a*>(row);
+        if (relmin < (uint32_t)EPL) o[relmin] = m.sv << 16;
+        if (relmax < (uint32_t)EPL) o[relmax] = m.sv & 0xFFFF0000u;
+#pragma unroll
+        for (int i = 0; i < EPL / 4; ++i) {
+            const uint4 a = row[i];
+            v[4 * i] = u2f(a.x);
+            v[4 * i + 1] = u2f(a.y);
+            v[4 * i + 2] = u2f(a.z);
+            v[4 * i + 3] = u2f(a.w);
+        }
+    }
+}
+
+template <int BITS, int EPL, int LPG, bool SR>
 __global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
                                                            uint8_t* __restrict__ out, Rec rec_out, float* __restrict__ sum_out,
                                                            uint32_t meta_fp32_in, uint32_t meta_fp32_out) {
+    constexpr int ROW = EPL / 4 + 1;  // uint4 per private patch row, one of padding: conflict-free 16-byte accesses
+    __shared__ uint4 lds[kBlock * ROW];
     const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
     if (L >= n_lanes) return;
     const uint32_t lig = threadIdx.x & (LPG - 1);
+    uint4* row = &lds[threadIdx.x * ROW];
     const MetaOffsets mo = meta_offsets<LPG, SR>(rec_in, L, meta_fp32_in != 0);
     // -0 is the identity of fp32 addition for every value including -0, so the chain below starts exactly at v_0
-    float acc[8];
+    float acc[EPL];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = -0.0f;
+    for (int j = 0; j < EPL; ++j) acc[j] = -0.0f;
+    auto add_peer = [&](const RawPlanes<EPL>& r, uint32_t mraw) {
+        const GroupMeta m = spread_meta<SR>(mraw, mo);
+        float v[EPL];
+        dequant_mix<BITS, EPL>(r, m.s, m.lo, v);
+        if (SR) patch_spikes<EPL>(m, lig, row, v);
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) acc[j] = __fadd_rn(acc[j], v[j]);
+    };
     int p = 0;
     // four peers at a time: all loads first, so their latencies overlap
     for (; p + 4 <= n_peers; p += 4) {
-        RawPlanes<8> r[4];
+        RawPlanes<EPL> r[4];
         uint32_t mraw[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            r[i] = load_planes<BITS, 8>(peers.base[p + i], rec_in, L);
+            r[i] = load_planes<BITS, EPL>(peers.base[p + i], rec_in, L);
             mraw[i] = *reinterpret_cast<const uint32_t*>(at32(peers.base[p + i], mo.at));
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const GroupMeta m = spread_meta<SR>(mraw[i], mo);
-            float v[8];
-            dequant8<BITS, SR>(r[i], m, lig, v);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] = __fadd_rn(acc[j], v[j]);
-        }
+        for (int i = 0; i < 4; ++i) add_peer(r[i], mraw[i]);
     }
     for (; p < n_peers; ++p) {
-        const RawPlanes<8> r = load_planes<BITS, 8>(peers.base[p], rec_in, L);
+        const RawPlanes<EPL> r = load_planes<BITS, EPL>(peers.base[p], rec_in, L);
         const uint32_t mraw = *reinterpret_cast<const uint32_t*>(at32(peers.base[p], mo.at));
-        const GroupMeta m = spread_meta<SR>(mraw, mo);
-        float v[8];
-        dequant8<BITS, SR>(r, m, lig, v);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) acc[j] = __fadd_rn(acc[j], v[j]);
+        add_peer(r, mraw);
     }
     if (sum_out) {
-        float4* dst = reinterpret_cast<float4*>(sum_out) + 2 * (uint64_t)L;
-        dst[0] = make_float4(acc[0], acc[1], acc[2], acc[3]);
-        dst[1] = make_float4(acc[4], acc[5], acc[6], acc[7]);
-    }
-    uint32_t w[4];
+        float4* dst = reinterpret_cast<float4*>(sum_out) + (EPL / 4) * (uint64_t)L;
 #pragma unroll
-    for (int d = 0; d < 4; ++d) w[d] = pack_bf16(acc[2 * d], acc[2 * d + 1]);
-    uint32_t c[2];
+        for (int i = 0; i < EPL / 4; ++i) dst[i] = make_float4(acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]);
+    }
+    uint32_t w[EPL / 2];
+#pragma unroll
+    for (int d = 0; d < EPL / 2; ++d) w[d] = pack_bf16(acc[2 * d], acc[2 * d + 1]);
+    uint32_t c[EPL / 4];
     GroupMeta m;
-    quantize_lane<BITS, 8, LPG, SR>(w, lig, meta_fp32_out != 0, c, m);
-    store_planes<BITS, 8>(out, rec_out, L, c);
+    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_fp32_out != 0, c, m);
+    store_planes<BITS, EPL>(out, rec_out, L, c);
     if (lig == 0) store_meta<SR>(out, rec_out, L / LPG, m, meta_fp32_out != 0);
 }
 
@@ -664,24 +786,24 @@ __global__ __launch_bounds__(kChunk) void k_dispatch_rank(const int32_t* __restr
 }
 
 // Quantize every token once, store the packed row K times.  `rec` holds the row's section offsets (align 16).
-template <int BITS, int EPL, int LPG, bool SR>
+// One wave tile = 2048 consecutive elements of x (rows are multiples of 32 elements, so a lane never straddles rows).
+template <int BITS, int LPG, bool SR>
 __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __restrict__ x, uint32_t n_lanes, uint32_t lanes_per_row,
                                                              uint32_t K, const int32_t* __restrict__ dest, uint8_t* __restrict__ send,
                                                              Rec rec, uint32_t row_bytes, uint32_t meta_fp32) {
-    const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
+    constexpr int EPL = kEplStream;
+    __shared__ uint4 lds[kWaves][64 * kRowU4];
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const uint32_t lig = lane & (LPG - 1);
+    const uint32_t tile = blockIdx.x * kWaves + wave;
+    if (tile * 64 >= n_lanes) return;
+    const TileIn cur = tile_load(x, (uint64_t)tile * 256, lane, n_lanes * 4 - tile * 256);
+    uint32_t w[16];
+    tile_transpose(cur, lds[wave], lane, w);
+    const uint32_t L = tile * 64 + lane;
     if (L >= n_lanes) return;
-    const uint32_t lig = threadIdx.x & (LPG - 1);
     const uint32_t t = L / lanes_per_row;
     const uint32_t r = L - t * lanes_per_row;  // lane inside the row
-    uint32_t w[EPL / 2];
-#pragma unroll
-    for (int i = 0; i < EPL / 8; ++i) {
-        const uint4 v = x[(uint64_t)L * (EPL / 8) + i];
-        w[4 * i] = v.x;
-        w[4 * i + 1] = v.y;
-        w[4 * i + 2] = v.z;
-        w[4 * i + 3] = v.w;
-    }
     uint32_t c[EPL / 4];
     GroupMeta m;
     quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_fp32 != 0, c, m);
@@ -759,11 +881,26 @@ static inline int launch_status() { return hipGetLastError() == hipSuccess ? FCV
 
 static inline unsigned grid_lanes(uint32_t n_lanes) { return (unsigned)((n_lanes + kBlock - 1) / kBlock); }
 
+// Number of blocks of a persistent launch: enough to fill the chip, at most one wave per tile.
+static unsigned persistent_grid(uint32_t n_tiles) {
+    static int blocks = 0;
+    if (blocks == 0) {
+        int dev = 0, cus = 256;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
+        int per_cu = 4;
+        if (const char* e = getenv("FCV2_BLOCKS_PER_CU")) per_cu = atoi(e) > 0 ? atoi(e) : per_cu;
+        blocks = cus * per_cu;
+    }
+    const unsigned need = (n_tiles + kWaves - 1) / kWaves;
+    return need < (unsigned)blocks ? need : (unsigned)blocks;
+}
+
 template <int BITS, int G, bool SR> struct LaunchQuantize {
     static int run(const void* x, uint64_t n, void* out, const Rec& rec, uint32_t meta_fp32, hipStream_t st) {
         constexpr int EPL = kEplStream;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
-        hipLaunchKernelGGL((k_quantize_pack_t<BITS, EPL, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
+        const uint32_t n_tiles = (n_lanes + 63) / 64;
+        hipLaunchKernelGGL((k_quantize_pack_t<BITS, G / EPL, SR>), dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
                            (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_fp32);
         return launch_status();
     }
@@ -772,17 +909,22 @@ template <int BITS, int G, bool SR> struct LaunchUnpack {
     static int run(const void* in, const Rec& rec, uint64_t n, void* out, uint32_t out_fp32, uint32_t meta_fp32, hipStream_t st) {
         constexpr int EPL = kEplStream;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
-        hipLaunchKernelGGL((k_unpack_dequant_t<BITS, EPL, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
-                           (const uint8_t*)in, rec, n_lanes, out, out_fp32, meta_fp32);
+        if (out_fp32)
+            hipLaunchKernelGGL((k_unpack_dequant_t<BITS, G / EPL, SR, true>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
+                               (const uint8_t*)in, rec, n_lanes, (uint4*)out, meta_fp32);
+        else
+            hipLaunchKernelGGL((k_unpack_dequant_t<BITS, G / EPL, SR, false>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
+                               (const uint8_t*)in, rec, n_lanes, (uint4*)out, meta_fp32);
         return launch_status();
     }
 };
 template <int BITS, int G, bool SR> struct LaunchReduce {
     static int run(const PeerPtrs& peers, int n_peers, uint64_t n, const Rec& rec_in, void* out, const Rec& rec_out,
                    float* sum_out, uint32_t mf_in, uint32_t mf_out, hipStream_t st) {
-        const uint32_t n_lanes = (uint32_t)(n / 8);
-        hipLaunchKernelGGL((k_reduce_requant<BITS, G / 8, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st, peers, n_peers,
-                           n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
+        constexpr int EPL = G >= 64 ? 16 : 8;
+        const uint32_t n_lanes = (uint32_t)(n / EPL);
+        hipLaunchKernelGGL((k_reduce_requant<BITS, EPL, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st, peers,
+                           n_peers, n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
         return launch_status();
     }
 };
@@ -791,7 +933,7 @@ template <int BITS, int G, bool SR> struct LaunchDispatch {
                    uint32_t row_bytes, uint32_t meta_fp32, hipStream_t st) {
         constexpr int EPL = kEplStream;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
-        hipLaunchKernelGGL((k_dispatch_quant_t<BITS, EPL, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
+        hipLaunchKernelGGL((k_dispatch_quant_t<BITS, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
                            (const uint4*)x, n_lanes, H / EPL, K, dest, send, rec, row_bytes, meta_fp32);
         return launch_status();
     }

@@ -125,6 +125,10 @@ def test_plane_packing_sequences_match_oracle(hc, bits):
             back = np.zeros(8, np.uint8)
             assert hc.hc_codes_of_planes(bits, out[2], out[3], out[4], back.ctypes.data_as(C.POINTER(C.c_uint8))) == 0
             assert np.array_equal(back, codes)
+        back = np.zeros(8, np.uint8)  # the "pair" decoding used with mixed-precision FMAs
+        assert hc.hc_pairs_of_planes(bits, out[0], out[1], out[2], out[3], out[4],
+                                     back.ctypes.data_as(C.POINTER(C.c_uint8))) == 0
+        assert np.array_equal(back, codes), (bits, codes, back)
 
 
 def test_bf16_helpers_match_oracle(hc):
