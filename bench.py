@@ -23,6 +23,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 LLC_BYTES = 256 << 20
+ALU_PEAK_TLOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # 39.3 T lane-operations/s: VALU issue without packed fp32
+# Measured with rocprofv3 counters at the headline shape (profiles/kernels_b3_g128_n8_pmc.md); per launch.
+TRAFFIC_BYTES = {"quantize_pack": 41.34e6, "reduce_requant": 74.87e6, "unpack_dequant": 41.19e6}
+VALU_OPS_PER_ELEMENT = {"quantize_pack": 18.0, "reduce_requant": 68.3, "unpack_dequant": 6.4}
 
 
 def packed_bytes(n, bits, group, spike=True):
@@ -87,68 +91,92 @@ def main():
         per_set = 2 * n * 2 + (n_peers + 2) * packed_bytes(n, bits, group)
         return max(4, -(-3 * LLC_BYTES // per_set))
 
-    def run_steps(sets, bits, steps, warmup, per_kernel):
-        """Times `steps` steps after `warmup`; returns (ms per step, {kernel: ms per launch})."""
+    def bind_calls(sets, bits):
+        """Arguments marshalled once per buffer set: a timed loop is C-ABI calls and nothing else."""
         import ctypes as C
         lib = fcv2.lib()
         fmt = fcv2._Fmt(bits, group, SR)
         stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
-        # arguments marshalled once per buffer set: the timed loop is three C-ABI calls per step and nothing else
         for s in sets:
             if s.get("bits") != bits:
                 arr = (C.c_void_p * n_peers)(*[p.data_ptr() for p in s["peers"]])
                 s["bits"] = bits
                 s["keep"] = (arr, fmt)
-                s["calls"] = (
-                    (lib.fcv2_quantize_pack, (C.c_void_p(s["x"].data_ptr()), n, C.byref(fmt), C.c_void_p(s["q"].data_ptr()), stream)),
-                    (lib.fcv2_reduce_requant, (arr, n_peers, n, C.byref(fmt), C.byref(fmt), C.c_void_p(s["r"].data_ptr()), None, stream)),
-                    (lib.fcv2_unpack_dequant, (C.c_void_p(s["r"].data_ptr()), n, C.byref(fmt), C.c_void_p(s["o"].data_ptr()), fcv2.DT_BF16, stream)),
+                s["calls"] = dict(
+                    quantize_pack=(lib.fcv2_quantize_pack, (C.c_void_p(s["x"].data_ptr()), n, C.byref(fmt), C.c_void_p(s["q"].data_ptr()), stream)),
+                    reduce_requant=(lib.fcv2_reduce_requant, (arr, n_peers, n, C.byref(fmt), C.byref(fmt), C.c_void_p(s["r"].data_ptr()), None, stream)),
+                    unpack_dequant=(lib.fcv2_unpack_dequant, (C.c_void_p(s["r"].data_ptr()), n, C.byref(fmt), C.c_void_p(s["o"].data_ptr()), fcv2.DT_BF16, stream)),
                 )
 
-        def step(s, marks=None):
-            for k, (fn, a) in enumerate(s["calls"]):
-                if marks is not None:
-                    marks[k].record()
-                rc = fn(*a)
-                if rc != 0:
-                    raise RuntimeError(f"libfcv2 call {k} failed: {rc}")
-            if marks is not None:
-                marks[3].record()
+    KERNELS = ("quantize_pack", "reduce_requant", "unpack_dequant")
 
+    def timed(fn, count, warmup):
+        """HIP events on the launch stream around `count` back-to-back calls; returns ms per call."""
         for i in range(warmup):
-            step(sets[i % len(sets)])
+            fn(i)
         torch.cuda.synchronize()
-        marks = [[ev() for _ in range(4)] for _ in range(steps)] if per_kernel else None
         t0, t1 = ev(), ev()
         t0.record()
-        for i in range(steps):
-            step(sets[i % len(sets)], marks[i] if per_kernel else None)
+        for i in range(count):
+            fn(i)
         t1.record()
         torch.cuda.synchronize()
-        ms = t0.elapsed_time(t1) / steps
-        kern = {}
-        if per_kernel:
-            for k, name in enumerate(("quantize_pack", "reduce_requant", "unpack_dequant")):
-                kern[name] = sum(m[k].elapsed_time(m[k + 1]) for m in marks) / steps
-        return ms, kern
+        return t0.elapsed_time(t1) / count
+
+    def call(s, name):
+        fn, a = s["calls"][name]
+        rc = fn(*a)
+        if rc != 0:
+            raise RuntimeError(f"libfcv2 {name} failed: {rc}")
+
+    def run_steps(sets, bits, steps, warmup):
+        """ms per step: one step = the three calls of the hot path, on rotating buffer sets."""
+        bind_calls(sets, bits)
+
+        def step(i):
+            s = sets[i % len(sets)]
+            for name in KERNELS:
+                call(s, name)
+
+        return timed(step, steps, warmup)
+
+    def run_kernels(sets, bits, steps, warmup):
+        """ms per launch of each kernel, each timed over its own run of `steps` back-to-back launches."""
+        bind_calls(sets, bits)
+        return {name: timed(lambda i, name=name: call(sets[i % len(sets)], name), steps, warmup) for name in KERNELS}
 
     # ---- headline: 3-bit ------------------------------------------------------------------------------------
     bits = 3
     sets = make_sets(bits, n_sets_for(bits))
-    ms_step, _ = run_steps(sets, bits, args.steps, args.warmup, per_kernel=False)  # the timed region proper
-    _, kern_ms = run_steps(sets, bits, args.steps, 2, per_kernel=True)             # same loop with per-kernel marks
+    ms_step = run_steps(sets, bits, args.steps, args.warmup)  # the timed region proper
+    kern_ms = run_kernels(sets, bits, args.steps, 3)           # the same launches, one kernel at a time
     ab = algo_bytes(bits)
     total_bytes = sum(ab.values())
     value = total_bytes / (ms_step * 1e-3) / 1e9
-    kernels = {k: dict(ms=round(kern_ms[k], 5), algorithmic_bytes=ab[k],
+    kernels = {k: dict(us=round(kern_ms[k] * 1e3, 2), algorithmic_bytes=ab[k],
                        gbs=round(ab[k] / (kern_ms[k] * 1e-3) / 1e9, 1),
                        frac_of_hbm_peak=round(ab[k] / (kern_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)) for k in ab}
     dom = "reduce_requant"
-    roofline = dict(bound="hbm", kernel=f"k_reduce_requant<3,16,true> ({dom}, N={n_peers})",
+    roofline = dict(bound="hbm", kernel=f"k_reduce_requant<3,16,8,true> ({dom}, N={n_peers})",
                     achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(kernels[dom]["gbs"] / HBM_PEAK_GBS, 4), traffic=None)
+                    frac=round(kernels[dom]["gbs"] / HBM_PEAK_GBS, 4), traffic=TRAFFIC_BYTES[dom],
+                    traffic_source="profiles/kernels_b3_g128_n8_pmc.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scaled by a copy of known size)")
+    # the same kernel against the bound that actually limits it at 3 bits: VALU issue (see DESIGN.md)
+    alu = dict(bound="alu", unit="T lane-op/s", peak=ALU_PEAK_TLOPS,
+               achieved=round(VALU_OPS_PER_ELEMENT[dom] * n / (kern_ms[dom] * 1e-3) / 1e12, 2),
+               note="VALU instructions per output element (rocprofv3 SQ_INSTS_VALU) x elements / duration; "
+                    "peak = 256 CU x 4 SIMD x 16 lanes x 2.4 GHz without packed fp32")
+    alu["frac"] = round(alu["achieved"] / ALU_PEAK_TLOPS, 4)
+    # practical streaming ceiling: the library's plain copy kernel on 256 MiB
+    import ctypes as C
+    ca = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+    cb = torch.empty_like(ca)
+    cstream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    ms_copy = timed(lambda i: fcv2.lib().fcv2_stream_copy(C.c_void_p(ca.data_ptr()), C.c_void_p(cb.data_ptr()), ca.numel(), cstream), 20, 3)
+    copy_gbs = 2 * ca.numel() / (ms_copy * 1e-3) / 1e9
+    del ca, cb
     # warm-cache figure for context: one buffer set, everything stays in the last-level cache
-    ms_warm, _ = run_steps(sets[:1], bits, args.steps, args.warmup, per_kernel=False)
+    ms_warm = run_steps(sets[:1], bits, args.steps, args.warmup)
     del sets
     torch.cuda.empty_cache()
 
@@ -157,7 +185,8 @@ def main():
     if not args.no_sweep:
         for b in (2, 3, 4, 5, 6, 7, 8):
             s = make_sets(b, n_sets_for(b))
-            ms_b, k_b = run_steps(s, b, max(10, args.steps // 2), 3, per_kernel=True)
+            ms_b = run_steps(s, b, max(10, args.steps // 2), 3)
+            k_b = run_kernels(s, b, max(10, args.steps // 2), 3)
             abb = algo_bytes(b)
             sweep[str(b)] = {k: dict(us=round(k_b[k] * 1e3, 2), gbs=round(abb[k] / (k_b[k] * 1e-3) / 1e9, 1),
                                      frac=round(abb[k] / (k_b[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)) for k in abb}
@@ -225,7 +254,8 @@ def main():
                    "buffer_sets_rotated": n_sets_for(3)},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "warm_cache_gbs": round(total_bytes / (ms_warm * 1e-3) / 1e9, 1),
-        "kernels": kernels, "roofline": roofline, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
+        "copy_ceiling_gbs": round(copy_gbs, 1),
+        "kernels": kernels, "roofline": roofline, "alu_roofline": alu, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
     }
     print(json.dumps(out))
 

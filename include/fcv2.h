@@ -106,7 +106,8 @@ int fcv2_reduce_requant(const void* const* peers_dev, int n_peers, uint64_t n, c
  *   row_src_dev   [T*K] int32 out: entry r < R is t*K+k of the copy stored in row r; inside an expert rows are
  *                 in ascending t*K+k (a stable counting sort)
  *   workspace_dev at least fcv2_dispatch_workspace_bytes(T, K, E) bytes of scratch, 16-byte aligned
- * Ids outside [-1, E) are treated as dropped. */
+ * Ids outside [-1, E) are treated as dropped.  Limits (FCV2_ERR_UNSUPPORTED beyond): E <= 2048, T*K < 2^24,
+ * T*K*row_bytes < 2^32 (a send buffer below 4 GiB). */
 int fcv2_dispatch_workspace_bytes(uint32_t T, uint32_t K, uint32_t E, size_t* out);
 int fcv2_dispatch_quant(const void* x_bf16_dev, const int32_t* topk_ids_dev, uint32_t T, uint32_t H, uint32_t K,
                         uint32_t E, const fcv2_fmt_t* fmt, void* send_buf_dev, int32_t* expert_offsets_dev,

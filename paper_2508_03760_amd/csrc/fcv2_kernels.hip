@@ -688,28 +688,41 @@ __global__ __launch_bounds__(kChunk) void k_dispatch_count(const int32_t* __rest
     for (uint32_t e = threadIdx.x; e < E; e += kChunk) hist[(uint64_t)blockIdx.x * E + e] = lds[e];
 }
 
+// Exclusive prefix sum of one value per thread over a block of 256 threads; *total gets the block sum.
+__device__ __forceinline__ int32_t block_exclusive_scan_256(int32_t v, int32_t* lds4, int32_t* total) {
+    const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int32_t up = __shfl_up(inc, d);
+        if ((int)lane >= d) inc += up;
+    }
+    if (lane == 63) lds4[wave] = inc;
+    __syncthreads();
+    int32_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const int32_t t = lds4[w];
+        if ((uint32_t)w < wave) before += t;
+        all += t;
+    }
+    *total = all;
+    __syncthreads();
+    return before + inc - v;
+}
+
 // One block per expert: exclusive prefix over the chunks, in place; totals[e] = count of expert e.
 __global__ __launch_bounds__(256) void k_dispatch_scan_chunks(int32_t* __restrict__ hist, uint32_t n_chunks, uint32_t E,
                                                               int32_t* __restrict__ totals) {
-    __shared__ int32_t part[256];
+    __shared__ int32_t lds4[4];
     const uint32_t e = blockIdx.x;
     const uint32_t per = (n_chunks + 255) / 256;  // consecutive chunks per thread
     const uint32_t c0 = threadIdx.x * per, c1 = min(c0 + per, n_chunks);
     int32_t s = 0;
     for (uint32_t c = c0; c < c1; ++c) s += hist[(uint64_t)c * E + e];
-    part[threadIdx.x] = s;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int32_t run = 0;
-        for (int t = 0; t < 256; ++t) {
-            const int32_t v = part[t];
-            part[t] = run;
-            run += v;
-        }
-        totals[e] = run;
-    }
-    __syncthreads();
-    int32_t run = part[threadIdx.x];
+    int32_t total;
+    int32_t run = block_exclusive_scan_256(s, lds4, &total);
+    if (threadIdx.x == 0) totals[e] = total;
     for (uint32_t c = c0; c < c1; ++c) {
         const int32_t v = hist[(uint64_t)c * E + e];
         hist[(uint64_t)c * E + e] = run;
@@ -717,41 +730,31 @@ __global__ __launch_bounds__(256) void k_dispatch_scan_chunks(int32_t* __restric
     }
 }
 
-// Exclusive scan of the expert totals into expert_offsets[E+1] (one block).
-__global__ __launch_bounds__(256) void k_dispatch_scan_experts(const int32_t* __restrict__ totals, uint32_t E,
-                                                               int32_t* __restrict__ expert_offsets) {
-    __shared__ int32_t part[256];
-    const uint32_t per = (E + 255) / 256;
-    const uint32_t e0 = threadIdx.x * per, e1 = min(e0 + per, E);
-    int32_t s = 0;
-    for (uint32_t e = e0; e < e1; ++e) s += totals[e];
-    part[threadIdx.x] = s;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int32_t run = 0;
-        for (int t = 0; t < 256; ++t) {
-            const int32_t v = part[t];
-            part[t] = run;
-            run += v;
-        }
-        expert_offsets[E] = run;
-    }
-    __syncthreads();
-    int32_t run = part[threadIdx.x];
-    for (uint32_t e = e0; e < e1; ++e) {
-        expert_offsets[e] = run;
-        run += totals[e];
-    }
-}
-
 // Destination row of every routed slot: expert start + copies in earlier chunks + copies earlier in this chunk.
+// Every block derives the expert starts (exclusive scan of the totals) itself; block 0 also publishes them.
 __global__ __launch_bounds__(kChunk) void k_dispatch_rank(const int32_t* __restrict__ ids, uint32_t n_slots, uint32_t E,
-                                                          const int32_t* __restrict__ hist,
-                                                          const int32_t* __restrict__ expert_offsets,
-                                                          int32_t* __restrict__ dest, int32_t* __restrict__ row_src) {
-    extern __shared__ int32_t lds[];  // [kChunk/64][E]: copies of expert e in each wave of this chunk
-    constexpr int kWaves = kChunk / 64;
-    for (uint32_t t = threadIdx.x; t < kWaves * E; t += kChunk) lds[t] = 0;
+                                                          const int32_t* __restrict__ hist, const int32_t* __restrict__ totals,
+                                                          int32_t* __restrict__ expert_offsets, int32_t* __restrict__ dest,
+                                                          int32_t* __restrict__ row_src) {
+    extern __shared__ int32_t lds[];  // [kChunk/64][E] copies of expert e in each wave of this chunk, then [E] expert starts
+    __shared__ int32_t lds4[4];
+    constexpr int kW = kChunk / 64;
+    int32_t* start = lds + kW * E;
+    for (uint32_t t = threadIdx.x; t < kW * E; t += kChunk) lds[t] = 0;
+    {   // expert starts: consecutive experts per thread, block scan of the per-thread sums
+        const uint32_t per = (E + kChunk - 1) / kChunk;
+        const uint32_t e0 = threadIdx.x * per, e1 = min(e0 + per, E);
+        int32_t s = 0;
+        for (uint32_t e = e0; e < e1; ++e) s += totals[e];
+        int32_t total;
+        int32_t run = block_exclusive_scan_256(s, lds4, &total);
+        for (uint32_t e = e0; e < e1; ++e) {
+            start[e] = run;
+            if (blockIdx.x == 0) expert_offsets[e] = run;
+            run += totals[e];
+        }
+        if (blockIdx.x == 0 && threadIdx.x == 0) expert_offsets[E] = total;
+    }
     __syncthreads();
     const uint32_t i = blockIdx.x * kChunk + threadIdx.x;
     const uint32_t wave = threadIdx.x / 64, lane = threadIdx.x & 63;
@@ -777,7 +780,7 @@ __global__ __launch_bounds__(kChunk) void k_dispatch_rank(const int32_t* __restr
     if (e >= 0) {
         uint32_t before = 0;
         for (uint32_t wv = 0; wv < wave; ++wv) before += lds[wv * E + e];
-        const int32_t r = expert_offsets[e] + hist[(uint64_t)blockIdx.x * E + e] + (int32_t)(before + rank);
+        const int32_t r = start[e] + hist[(uint64_t)blockIdx.x * E + e] + (int32_t)(before + rank);
         dest[i] = r;
         row_src[r] = (int32_t)i;
     } else if (i < n_slots) {
@@ -808,12 +811,49 @@ __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __rest
     GroupMeta m;
     quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_fp32 != 0, c, m);
     const uint32_t g = r / LPG;
-    for (uint32_t k = 0; k < K; ++k) {
-        const int32_t row = dest[t * K + k];
-        if (row < 0) continue;
-        uint8_t* base = send + (uint64_t)(uint32_t)row * row_bytes;
-        store_planes<BITS, EPL>(base, rec, r, c);
-        if (lig == 0) store_meta<SR>(base, rec, g, m, meta_fp32 != 0);
+    // The send buffer is addressed with 32-bit offsets (checked on the host): a row's offset is one 24-bit multiply,
+    // every store one add on top of per-lane offsets computed once.
+    using P = Planes<BITS>;
+    constexpr int U = EPL / 8;
+    uint32_t q4[U], q2[U], q1 = 0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        q4[u] = P::w4 ? pack_plane4<P::sh4, BITS>(c[2 * u], c[2 * u + 1]) : 0u;
+        q2[u] = P::w2 ? (pack_plane2<P::sh2, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFFFu) : 0u;
+        if (P::w1) q1 |= (pack_plane1<P::sh1, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFu) << (8 * u);
+    }
+    const uint32_t o8 = rec.plane8 + 32u * r, o4 = rec.plane4 + 16u * r, o2 = rec.plane2 + 8u * r, o1 = rec.plane1 + 4u * r;
+    const uint32_t msz = meta_fp32 ? 4u : 2u;
+    const uint32_t os = rec.scale + msz * g, oz = rec.zero + msz * g, ov = rec.spike_val + 4u * g, oi = rec.spike_idx + 2u * g;
+    for (uint32_t k0 = 0; k0 < K; k0 += 8) {
+        int32_t rows[8];  // all destinations first: the loads overlap instead of queueing one behind the other
+#pragma unroll
+        for (int i = 0; i < 8; ++i) rows[i] = (k0 + i < K) ? dest[t * K + k0 + i] : -1;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            if (rows[i] < 0) continue;
+            const uint32_t ro = __umul24((uint32_t)rows[i], row_bytes);
+            if (P::w8) {
+                *reinterpret_cast<uint4*>(send + (ro + o8)) = make_uint4(c[0], c[1], c[2], c[3]);
+                *reinterpret_cast<uint4*>(send + (ro + o8 + 16u)) = make_uint4(c[4], c[5], c[6], c[7]);
+            }
+            if (P::w4) *reinterpret_cast<uint4*>(send + (ro + o4)) = make_uint4(q4[0], q4[1], q4[2], q4[3]);
+            if (P::w2) *reinterpret_cast<uint2*>(send + (ro + o2)) = make_uint2(q2[0] | (q2[1] << 16), q2[2] | (q2[3] << 16));
+            if (P::w1) *reinterpret_cast<uint32_t*>(send + (ro + o1)) = q1;
+            if (lig == 0) {
+                if (meta_fp32) {
+                    *reinterpret_cast<float*>(send + (ro + os)) = m.s;
+                    *reinterpret_cast<float*>(send + (ro + oz)) = m.lo;
+                } else {
+                    *reinterpret_cast<uint16_t*>(send + (ro + os)) = (uint16_t)(f2u(m.s) >> 16);
+                    *reinterpret_cast<uint16_t*>(send + (ro + oz)) = (uint16_t)(f2u(m.lo) >> 16);
+                }
+                if (SR) {
+                    *reinterpret_cast<uint32_t*>(send + (ro + ov)) = m.sv;
+                    *reinterpret_cast<uint16_t*>(send + (ro + oi)) = (uint16_t)m.si;
+                }
+            }
+        }
     }
 }
 
@@ -1061,7 +1101,7 @@ int fcv2_reduce_requant(const void* const* peers, int n_peers, uint64_t n, const
 int fcv2_dispatch_workspace_bytes(uint32_t T, uint32_t K, uint32_t E, size_t* out) {
     if (!out || T == 0 || K == 0 || E == 0) return FCV2_ERR_INVALID_ARG;
     if ((uint64_t)T * K > 0x7FFFFFFFull) return FCV2_ERR_INVALID_ARG;
-    if (E > 8192) return FCV2_ERR_UNSUPPORTED;  // per-wave expert counters live in LDS
+    if (E > 2048) return FCV2_ERR_UNSUPPORTED;  // per-wave expert counters and expert starts live in LDS (40 KiB at most)
     *out = dispatch_ws(T, K, E).bytes;
     return FCV2_OK;
 }
@@ -1076,6 +1116,9 @@ int fcv2_dispatch_quant(const void* x, const int32_t* ids, uint32_t T, uint32_t 
     rc = fcv2_get_layout(H, fmt, FCV2_ROW_ALIGN, &l);
     if (rc != FCV2_OK) return rc;
     if ((uint64_t)T * H > kMaxElems) return FCV2_ERR_UNSUPPORTED;
+    // rows are addressed with 24-bit row numbers and 32-bit byte offsets inside the send buffer
+    if ((uint64_t)T * K >= (1u << 24) || l.total_bytes >= (1u << 24) || (uint64_t)T * K * l.total_bytes > 0xFFFFFFFFull)
+        return FCV2_ERR_UNSUPPORTED;
     if (ws_bytes < need) return FCV2_ERR_WORKSPACE;
     if (!aligned16(x) || !aligned16(send) || !aligned16(ws) || ((uintptr_t)ids & 3u) || ((uintptr_t)expert_offsets & 3u) ||
         ((uintptr_t)row_src & 3u))
@@ -1087,9 +1130,8 @@ int fcv2_dispatch_quant(const void* x, const int32_t* ids, uint32_t T, uint32_t 
     int32_t* dest = (int32_t*)((uint8_t*)ws + w.off_dest);
     hipLaunchKernelGGL(k_dispatch_count, dim3(w.n_chunks), dim3(kChunk), E * 4, st, ids, w.n_slots, E, hist);
     hipLaunchKernelGGL(k_dispatch_scan_chunks, dim3(E), dim3(256), 0, st, hist, w.n_chunks, E, totals);
-    hipLaunchKernelGGL(k_dispatch_scan_experts, dim3(1), dim3(256), 0, st, totals, E, expert_offsets);
-    hipLaunchKernelGGL(k_dispatch_rank, dim3(w.n_chunks), dim3(kChunk), (kChunk / 64) * E * 4, st, ids, w.n_slots, E, hist,
-                       expert_offsets, dest, row_src);
+    hipLaunchKernelGGL(k_dispatch_rank, dim3(w.n_chunks), dim3(kChunk), (kChunk / 64 + 1) * E * 4, st, ids, w.n_slots, E, hist,
+                       (const int32_t*)totals, expert_offsets, dest, row_src);
     if (launch_status() != FCV2_OK) return FCV2_ERR_LAUNCH;
     return by_format<LaunchDispatch>(fmt, x, (uint64_t)T * H, H, K, (const int32_t*)dest, (uint8_t*)send,
                                      rec_of(l), (uint32_t)l.total_bytes, (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0), st);
