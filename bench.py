@@ -227,6 +227,53 @@ def main():
         del bufs, x3
         torch.cuda.empty_cache()
 
+    # ---- decode-sized latency case (workload 5) and the large AllReduce payload (workload 4) --------------------
+    latency, large = {}, {}
+    if not args.no_sweep:
+        import ctypes as C
+        lib = fcv2.lib()
+        stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        w5 = W.WORKLOADS[5]
+        n5 = w5["rows"] * w5["cols"]
+        x5 = bf16(W.tensor(5, 0).reshape(-1))
+        peers5 = [bf16(W.tensor(5, p).reshape(-1)) for p in range(8)]
+        for b in w5["bits"]:
+            fmt5 = fcv2._Fmt(b, 128, SR)
+            L5 = fcv2.get_layout(n5, b, 128, SR)
+            q5 = torch.zeros(L5.total_bytes, dtype=torch.uint8, device=dev)
+            o5 = torch.empty(n5, dtype=torch.bfloat16, device=dev)
+            pk5 = [fcv2.quantize_pack(x, b, 128, SR) for x in peers5]
+            arr5 = (C.c_void_p * 8)(*[p.data_ptr() for p in pk5])
+            P5 = packed_bytes(n5, b, 128)
+            calls = dict(
+                quantize_pack=(lambda i: lib.fcv2_quantize_pack(C.c_void_p(x5.data_ptr()), n5, C.byref(fmt5), C.c_void_p(q5.data_ptr()), stream), 2 * n5 + P5),
+                unpack_dequant=(lambda i: lib.fcv2_unpack_dequant(C.c_void_p(pk5[0].data_ptr()), n5, C.byref(fmt5), C.c_void_p(o5.data_ptr()), fcv2.DT_BF16, stream), 2 * n5 + P5),
+                reduce_requant=(lambda i: lib.fcv2_reduce_requant(arr5, 8, n5, C.byref(fmt5), C.byref(fmt5), C.c_void_p(q5.data_ptr()), None, stream), 9 * P5))
+            latency[str(b)] = {k: dict(us_per_call=round(timed(f, 1000, 20) * 1e3, 2)) for k, (f, _) in calls.items()}
+            for k, (_, nbytes) in calls.items():
+                latency[str(b)][k]["gbs"] = round(nbytes / (latency[str(b)][k]["us_per_call"] * 1e-6) / 1e9, 1)
+        del x5, peers5
+        w4 = W.WORKLOADS[4]
+        n4 = w4["rows"] * w4["cols"]
+        xs4 = [bf16(W.tensor(4, p).reshape(-1)) for p in range(8)]
+        for b in w4["bits"]:
+            for g in w4["groups"]:
+                fmt4 = fcv2._Fmt(b, g, SR)
+                L4 = fcv2.get_layout(n4, b, g, SR)
+                pk4 = [fcv2.quantize_pack(x, b, g, SR) for x in xs4]
+                q4 = torch.zeros(L4.total_bytes, dtype=torch.uint8, device=dev)
+                arr4 = (C.c_void_p * 8)(*[p.data_ptr() for p in pk4])
+                P4 = packed_bytes(n4, b, g)
+                us_q = timed(lambda i: lib.fcv2_quantize_pack(C.c_void_p(xs4[i % 8].data_ptr()), n4, C.byref(fmt4), C.c_void_p(q4.data_ptr()), stream), 16, 2) * 1e3
+                us_r = timed(lambda i: lib.fcv2_reduce_requant(arr4, 8, n4, C.byref(fmt4), C.byref(fmt4), C.c_void_p(q4.data_ptr()), None, stream), 16, 2) * 1e3
+                large[f"b{b}_g{g}"] = dict(
+                    quantize_pack=dict(us=round(us_q, 1), gbs=round((2 * n4 + P4) / us_q / 1e3, 1), frac=round((2 * n4 + P4) / us_q / 1e3 / HBM_PEAK_GBS, 4)),
+                    reduce_requant=dict(us=round(us_r, 1), gbs=round(9 * P4 / us_r / 1e3, 1), frac=round(9 * P4 / us_r / 1e3 / HBM_PEAK_GBS, 4)))
+                del pk4, q4
+                torch.cuda.empty_cache()
+        del xs4
+        torch.cuda.empty_cache()
+
     # ---- the CPU oracle on the same workload, timed on the host -------------------------------------------------
     cpu = None
     if not args.no_cpu:
@@ -256,6 +303,7 @@ def main():
         "warm_cache_gbs": round(total_bytes / (ms_warm * 1e-3) / 1e9, 1),
         "copy_ceiling_gbs": round(copy_gbs, 1),
         "kernels": kernels, "roofline": roofline, "alu_roofline": alu, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
+        "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
     }
     print(json.dumps(out))
 
