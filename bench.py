@@ -24,7 +24,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 LLC_BYTES = 256 << 20
 ALU_PEAK_TLOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # 39.3 T lane-operations/s: VALU issue without packed fp32
-# Measured with rocprofv3 counters at the headline shape (profiles/kernels_b3_g128_n8_pmc.md); per launch.
+# Measured with rocprofv3 counters at the headline shape (profiles/headline_step_b3_g128_n8.md); per launch.
 TRAFFIC_BYTES = {"quantize_pack": 41.34e6, "reduce_requant": 74.87e6, "unpack_dequant": 41.19e6}
 VALU_OPS_PER_ELEMENT = {"quantize_pack": 18.0, "reduce_requant": 68.3, "unpack_dequant": 6.4}
 
@@ -160,7 +160,7 @@ def main():
     roofline = dict(bound="hbm", kernel=f"k_reduce_requant<3,16,8,true> ({dom}, N={n_peers})",
                     achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(kernels[dom]["gbs"] / HBM_PEAK_GBS, 4), traffic=TRAFFIC_BYTES[dom],
-                    traffic_source="profiles/kernels_b3_g128_n8_pmc.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scaled by a copy of known size)")
+                    traffic_source="profiles/headline_step_b3_g128_n8.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scaled by a copy of known size)")
     # the same kernel against the bound that actually limits it at 3 bits: VALU issue
     alu = dict(bound="alu", unit="T lane-op/s", peak=ALU_PEAK_TLOPS,
                achieved=round(VALU_OPS_PER_ELEMENT[dom] * n / (kern_ms[dom] * 1e-3) / 1e12, 2),
