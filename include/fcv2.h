@@ -91,8 +91,8 @@ int fcv2_unpack_dequant(const void* packed_dev, uint64_t n, const fcv2_fmt_t* fm
  * round the sum to bf16 and quantize it again with fmt_out into packed_out_dev.
  * peers_dev is a HOST array of n_peers DEVICE pointers (copied at call time), 1 <= n_peers <= FCV2_MAX_PEERS.
  * sum_out_dev, if not NULL, receives the n fp32 sums (before the bf16 rounding).
- * fmt_in and fmt_out must agree in bits, group and FCV2_F_SPIKE (FCV2_F_META_FP32 may differ); other pairs
- * give FCV2_ERR_UNSUPPORTED. */
+ * fmt_in and fmt_out must agree in group and FCV2_F_SPIKE (bits and FCV2_F_META_FP32 may differ; equal bits take
+ * the fast kernel); other pairs give FCV2_ERR_UNSUPPORTED. */
 int fcv2_reduce_requant(const void* const* peers_dev, int n_peers, uint64_t n, const fcv2_fmt_t* fmt_in,
                         const fcv2_fmt_t* fmt_out, void* packed_out_dev, float* sum_out_dev, void* hip_stream);
 

@@ -670,6 +670,64 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n
     if (lig == 0) store_meta<SR>(out, rec_out, L / LPG, m, meta_fp32_out != 0);
 }
 
+// The same step when the peers' bit width differs from the output's: the input width is a run-time value
+// (one uniform switch per peer), the output width stays a template parameter.  Not pipelined; a compatibility
+// path next to the specialised kernel above.
+template <int BITS_OUT, int EPL, int LPG, bool SR>
+__global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers, int n_peers, uint32_t bits_in, uint32_t n_lanes,
+                                                                 Rec rec_in, uint8_t* __restrict__ out, Rec rec_out,
+                                                                 float* __restrict__ sum_out, uint32_t meta_fp32_in,
+                                                                 uint32_t meta_fp32_out) {
+    constexpr int ROW = EPL / 4 + 1;
+    __shared__ uint4 lds[kBlock * ROW];
+    const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
+    if (L >= n_lanes) return;
+    const uint32_t lig = threadIdx.x & (LPG - 1);
+    uint4* row = &lds[threadIdx.x * ROW];
+    const MetaOffsets mo = meta_offsets<LPG, SR>(rec_in, L, meta_fp32_in != 0);
+    float acc[EPL];
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) acc[j] = -0.0f;
+    for (int p = 0; p < n_peers; ++p) {
+        const uint8_t* base = peers.base[p];
+        const GroupMeta m = spread_meta<SR>(*reinterpret_cast<const uint32_t*>(at32(base, mo.at)), mo);
+        float v[EPL];
+        switch (bits_in) {
+#define FCV2_CASE(B)                                                      \
+    case B: {                                                             \
+        const RawPlanes<EPL> r = load_planes<B, EPL>(base, rec_in, L);    \
+        dequant_mix<B, EPL>(r, m.s, m.lo, v);                             \
+        break;                                                            \
+    }
+            FCV2_CASE(2)
+            FCV2_CASE(3)
+            FCV2_CASE(4)
+            FCV2_CASE(5)
+            FCV2_CASE(6)
+            FCV2_CASE(7)
+            default:
+                FCV2_CASE(8)
+#undef FCV2_CASE
+        }
+        if (SR) patch_spikes<EPL>(m, lig, row, v);
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) acc[j] = __fadd_rn(acc[j], v[j]);
+    }
+    if (sum_out) {
+        float4* dst = reinterpret_cast<float4*>(sum_out) + (EPL / 4) * (uint64_t)L;
+#pragma unroll
+        for (int i = 0; i < EPL / 4; ++i) dst[i] = make_float4(acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]);
+    }
+    uint32_t w[EPL / 2];
+#pragma unroll
+    for (int d = 0; d < EPL / 2; ++d) w[d] = pack_bf16(acc[2 * d], acc[2 * d + 1]);
+    uint32_t c[EPL / 4];
+    GroupMeta m;
+    quantize_lane<BITS_OUT, EPL, LPG, SR>(w, lig, meta_fp32_out != 0, c, m);
+    store_planes<BITS_OUT, EPL>(out, rec_out, L, c);
+    if (lig == 0) store_meta<SR>(out, rec_out, L / LPG, m, meta_fp32_out != 0);
+}
+
 // ---- dispatch: stable counting sort of the routed copies by expert, then quantize-and-scatter ------------------------
 constexpr int kChunk = 256;  // routed slots per block in the planning kernels
 
@@ -968,6 +1026,16 @@ template <int BITS, int G, bool SR> struct LaunchReduce {
         return launch_status();
     }
 };
+template <int BITS, int G, bool SR> struct LaunchReduceMixed {  // BITS = output width
+    static int run(const PeerPtrs& peers, int n_peers, uint32_t bits_in, uint64_t n, const Rec& rec_in, void* out,
+                   const Rec& rec_out, float* sum_out, uint32_t mf_in, uint32_t mf_out, hipStream_t st) {
+        constexpr int EPL = G >= 64 ? 16 : 8;
+        const uint32_t n_lanes = (uint32_t)(n / EPL);
+        hipLaunchKernelGGL((k_reduce_requant_mixed<BITS, EPL, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
+                           peers, n_peers, bits_in, n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
+        return launch_status();
+    }
+};
 template <int BITS, int G, bool SR> struct LaunchDispatch {
     static int run(const void* x, uint64_t n, uint32_t H, uint32_t K, const int32_t* dest, uint8_t* send, const Rec& rec,
                    uint32_t row_bytes, uint32_t meta_fp32, hipStream_t st) {
@@ -1082,8 +1150,7 @@ int fcv2_reduce_requant(const void* const* peers, int n_peers, uint64_t n, const
     rc = fcv2_get_layout(n, fmt_out, FCV2_TENSOR_ALIGN, &lout);
     if (rc != FCV2_OK) return rc;
     if (n > kMaxElems) return FCV2_ERR_UNSUPPORTED;
-    if (fmt_in->bits != fmt_out->bits || fmt_in->group != fmt_out->group ||
-        ((fmt_in->flags ^ fmt_out->flags) & FCV2_F_SPIKE) != 0)
+    if (fmt_in->group != fmt_out->group || ((fmt_in->flags ^ fmt_out->flags) & FCV2_F_SPIKE) != 0)
         return FCV2_ERR_UNSUPPORTED;
     if (!aligned16(packed_out) || (sum_out && !aligned16(sum_out))) return FCV2_ERR_ALIGN;
     PeerPtrs pp;
@@ -1093,9 +1160,13 @@ int fcv2_reduce_requant(const void* const* peers, int n_peers, uint64_t n, const
         if (!aligned16(ptr)) return FCV2_ERR_ALIGN;
         pp.base[p] = (const uint8_t*)ptr;
     }
-    return by_format<LaunchReduce>(fmt_in, pp, n_peers, n, rec_of(lin), packed_out, rec_of(lout), sum_out,
-                                   (uint32_t)((fmt_in->flags & FCV2_F_META_FP32) != 0),
-                                   (uint32_t)((fmt_out->flags & FCV2_F_META_FP32) != 0), (hipStream_t)stream);
+    const uint32_t mf_in = (uint32_t)((fmt_in->flags & FCV2_F_META_FP32) != 0);
+    const uint32_t mf_out = (uint32_t)((fmt_out->flags & FCV2_F_META_FP32) != 0);
+    if (fmt_in->bits != fmt_out->bits)
+        return by_format<LaunchReduceMixed>(fmt_out, pp, n_peers, fmt_in->bits, n, rec_of(lin), packed_out, rec_of(lout), sum_out,
+                                            mf_in, mf_out, (hipStream_t)stream);
+    return by_format<LaunchReduce>(fmt_in, pp, n_peers, n, rec_of(lin), packed_out, rec_of(lout), sum_out, mf_in, mf_out,
+                                   (hipStream_t)stream);
 }
 
 int fcv2_dispatch_workspace_bytes(uint32_t T, uint32_t K, uint32_t E, size_t* out) {

@@ -156,10 +156,10 @@ def test_every_scale_value(bits):
 
 # ---- reduce_requant -----------------------------------------------------------------------------------------------
 
-def check_reduce(xs, bits, group, flags, what, flags_out=None):
+def check_reduce(xs, bits, group, flags, what, flags_out=None, bits_out=None):
     n = xs[0].size
     fin = (bits, group, flags)
-    fout = (bits, group, flags if flags_out is None else flags_out)
+    fout = (bits if bits_out is None else bits_out, group, flags if flags_out is None else flags_out)
     peers_o = [O.quantize_pack(x, *fin) for x in xs]
     peers_g = [torch.from_numpy(p).to(DEV) for p in peers_o]
     want, s_want = O.reduce_requant(peers_o, n, fin, fout, want_sum=True)
@@ -187,6 +187,15 @@ def test_reduce_requant_peer_counts(n_peers):
     xs = [W.tensor(4, p, rows=1, cols=n).reshape(-1) for p in range(n_peers)]
     check_reduce(xs, 3, 128, SR, f"N{n_peers}")
     check_reduce(xs, 6, 64, SR | F32, f"N{n_peers} fp32 meta", flags_out=SR)
+
+
+@pytest.mark.parametrize("bits_in,bits_out", [(2, 8), (3, 5), (4, 3), (5, 2), (6, 7), (7, 4), (8, 6)])
+def test_reduce_requant_other_output_width(bits_in, bits_out):
+    n = 2048 * 2 + 512
+    for group in (32, 128):
+        xs = [W.tensor(2, p, rows=1, cols=n).reshape(-1) for p in range(5)]
+        check_reduce(xs, bits_in, group, SR, f"in b{bits_in} out b{bits_out} g{group}", bits_out=bits_out)
+    check_reduce(xs[:2], bits_in, 64, 0, f"in b{bits_in} out b{bits_out} no-sr", bits_out=bits_out, flags_out=F32)
 
 
 def test_reduce_requant_edge_cases():

@@ -93,7 +93,9 @@ def test_null_and_misaligned_arguments_are_refused_on_the_host(lib):
     peers = (vp * 2)(256, 512)
     assert lib.fcv2_reduce_requant(peers, 0, 4096, C.byref(fmt), C.byref(fmt), vp(1024), None, None) == -1
     assert lib.fcv2_reduce_requant(peers, 17, 4096, C.byref(fmt), C.byref(fmt), vp(1024), None, None) == -1
-    other = _Fmt(5, 128, 1)
+    other = _Fmt(4, 64, 1)  # another group size
+    assert lib.fcv2_reduce_requant(peers, 2, 4096, C.byref(fmt), C.byref(other), vp(1024), None, None) == -2
+    other = _Fmt(4, 128, 0)  # spike reserving on one side only
     assert lib.fcv2_reduce_requant(peers, 2, 4096, C.byref(fmt), C.byref(other), vp(1024), None, None) == -2
     lib.fcv2_dispatch_quant.argtypes = [vp, vp, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(_Fmt), vp, vp,
                                         vp, vp, C.c_size_t, vp]
