@@ -227,6 +227,32 @@ def main():
         del bufs, x3
         torch.cuda.empty_cache()
 
+    # ---- one rank's share of a whole two-step AllReduce over 8 ranks on the headline payload ------------------------
+    two_step = None
+    if not args.no_sweep:
+        R = n_peers
+        m = n // R
+        send = [fcv2.quantize_pack_slices(x, R, 3, group, SR) for x in xs]          # what the 8 ranks would send
+        mine = [[send[r][j] for r in range(R)] for j in range(R)]                    # copies of slice j, as received
+        red = [fcv2.reduce_requant(mine[j], m, (3, group, SR)) for j in range(R)]    # what the 8 ranks would return
+        out_t = torch.empty(n, dtype=torch.bfloat16, device=dev)
+        sbuf = torch.zeros_like(send[0])
+
+        def rank_step(i):
+            fcv2.quantize_pack_slices(xs[i % R], R, 3, group, SR, out=sbuf)              # pack my payload as 8 slices
+            fcv2.reduce_requant(mine[i % R], m, (3, group, SR), out=red[i % R])          # reduce my slice over 8 peers
+            fcv2.unpack_dequant_slices(red, n, 3, group, SR, torch.bfloat16, out=out_t)  # unpack the 8 reduced slices
+
+        ms_ts = timed(rank_step, max(20, args.steps // 2), 3)
+        P1 = packed_bytes(m, 3, group)
+        bytes_ts = (2 * n + R * P1) + (R + 1) * P1 + (R * P1 + 2 * n)
+        two_step = dict(ranks=R, us_per_rank=round(ms_ts * 1e3, 2), algorithmic_bytes=bytes_ts,
+                        gbs=round(bytes_ts / (ms_ts * 1e-3) / 1e9, 1),
+                        note="quantize_pack_slices(16M) + reduce_requant(2M x 8 peers) + unpack_dequant_slices(16M); "
+                             "exchanges between ranks are not part of a one-GPU run")
+        del send, mine, red, out_t, sbuf
+        torch.cuda.empty_cache()
+
     # ---- decode-sized latency case (workload 5) and the large AllReduce payload (workload 4) --------------------
     latency, large = {}, {}
     if not args.no_sweep:
@@ -303,7 +329,7 @@ def main():
         "warm_cache_gbs": round(total_bytes / (ms_warm * 1e-3) / 1e9, 1),
         "copy_ceiling_gbs": round(copy_gbs, 1),
         "kernels": kernels, "roofline": roofline, "alu_roofline": alu, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
-        "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
+        "two_step_allreduce_rank_share": two_step, "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
     }
     print(json.dumps(out))
 

@@ -86,6 +86,20 @@ int fcv2_quantize_pack(const void* x_bf16_dev, uint64_t n, const fcv2_fmt_t* fmt
 int fcv2_unpack_dequant(const void* packed_dev, uint64_t n, const fcv2_fmt_t* fmt, void* out_dev, int out_dtype,
                         void* hip_stream);
 
+/* The two exchanges of the two-step AllReduce (Sections 3.1, 3.4) move slices: rank r cuts its payload of n
+ * elements into n_slices equal slices and sends slice j to rank j; after the local reduce every rank collects the
+ * n_slices reduced slices.  These two calls are the sender and receiver sides with one launch each.
+ *   fcv2_quantize_pack_slices: slice j of x becomes a packed record of n/n_slices elements at
+ *     packed_dev + j * record_stride (record_stride >= that record's total_bytes, a multiple of 256).
+ *   fcv2_unpack_dequant_slices: records_dev is a HOST array of n_slices DEVICE pointers, record j holds slice j
+ *     of the output tensor of n elements.
+ * 1 <= n_slices <= FCV2_MAX_PEERS; n % n_slices == 0; a slice is a whole number of groups and, for
+ * n_slices > 1, a multiple of 2048 elements (FCV2_ERR_INVALID_ARG otherwise).  n_slices == 1 is the plain call. */
+int fcv2_quantize_pack_slices(const void* x_bf16_dev, uint64_t n, uint32_t n_slices, const fcv2_fmt_t* fmt,
+                              void* packed_dev, uint64_t record_stride, void* hip_stream);
+int fcv2_unpack_dequant_slices(const void* const* records_dev, uint32_t n_slices, uint64_t n, const fcv2_fmt_t* fmt,
+                               void* out_dev, int out_dtype, void* hip_stream);
+
 /* Local step of the two-step quantized AllReduce (Sections 3.1, 3.4): dequantize the n_peers packed chunks
  * (all of format fmt_in, all resident in this GPU's memory), add them in fp32 in peer order 0..n_peers-1,
  * round the sum to bf16 and quantize it again with fmt_out into packed_out_dev.

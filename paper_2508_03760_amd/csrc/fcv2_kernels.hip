@@ -446,7 +446,10 @@ __device__ __forceinline__ void tile_transpose(const TileIn& t, uint4* wave_lds,
 // quantized, so memory and arithmetic overlap inside every wave.
 template <int BITS, int LPG, bool SR>
 __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restrict__ x, uint32_t n_lanes, uint8_t* __restrict__ out,
-                                                            Rec rec, uint32_t meta_fp32) {
+                                                            Rec rec, uint32_t meta_fp32, uint32_t slice_lanes,
+                                                            uint64_t record_stride) {
+    // The tensor may be cut into equal slices, each packed into a record of its own (records `record_stride` bytes
+    // apart); slice_lanes is a multiple of 64 then, so a wave's tile lies in one slice.  One slice: slice_lanes = n_lanes.
     constexpr int EPL = kEplStream;
     __shared__ uint4 lds[kWaves][64 * kRowU4];
     const uint32_t lane = threadIdx.x & 63;
@@ -460,13 +463,16 @@ __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restr
     auto process = [&](const TileIn& t, uint32_t tl) {
         uint32_t w[16];
         tile_transpose(t, lds[wave], lane, w);
+        const uint32_t slice = (tl * 64) / slice_lanes;  // uniform
         const uint32_t L = tl * 64 + lane;
         if (L < n_lanes) {  // groups never straddle the end: whole groups are in or out together
             uint32_t c[EPL / 4];
             GroupMeta m;
             quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_fp32 != 0, c, m);
-            store_planes<BITS, EPL>(out, rec, L, c);
-            if (lig == 0) store_meta<SR>(out, rec, L / LPG, m, meta_fp32 != 0);
+            uint8_t* o = out + slice * record_stride;
+            const uint32_t Lr = L - slice * slice_lanes;  // lane inside the record
+            store_planes<BITS, EPL>(o, rec, Lr, c);
+            if (lig == 0) store_meta<SR>(o, rec, Lr / LPG, m, meta_fp32 != 0);
         }
     };
     // Two tiles are kept in flight per wave (two register sets, ping-pong, so loaded data is never moved); the
@@ -494,7 +500,7 @@ __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restr
 // (a) the two spikes of a group are dropped into place by plain indexed LDS writes of the lanes that own their
 // positions (Section 3.3: restored in place) and (b) the global stores are fully coalesced 16-byte pieces.
 template <int BITS, int LPG, bool SR, bool OUT_FP32>
-__global__ __launch_bounds__(kBlock) void k_unpack_dequant_t(const uint8_t* __restrict__ in, Rec rec, uint32_t n_lanes,
+__global__ __launch_bounds__(kBlock) void k_unpack_dequant_t(PeerPtrs records, uint32_t slice_lanes, Rec rec, uint32_t n_lanes,
                                                              uint4* __restrict__ out, uint32_t meta_fp32) {
     constexpr int EPL = kEplStream;
     constexpr int ROW = OUT_FP32 ? 9 : kRowU4;  // uint4 per lane row incl. one of padding
@@ -505,9 +511,13 @@ __global__ __launch_bounds__(kBlock) void k_unpack_dequant_t(const uint8_t* __re
     const uint32_t tile = blockIdx.x * kWaves + wave;
     const uint32_t L = tile * 64 + lane;
     uint4* row = &lds[wave][lane * ROW];
+    // The input may be several records, one per equal slice of the output (slice_lanes a multiple of 64 then).
+    const uint32_t slice = (uint32_t)__builtin_amdgcn_readfirstlane((int)((tile * 64) / slice_lanes));
     if (L < n_lanes) {
-        const uint32_t g = L / LPG;
-        const RawPlanes<EPL> r = load_planes<BITS, EPL>(in, rec, L);
+        const uint8_t* __restrict__ in = records.base[slice];
+        const uint32_t Lr = L - slice * slice_lanes;  // lane inside the record
+        const uint32_t g = Lr / LPG;
+        const RawPlanes<EPL> r = load_planes<BITS, EPL>(in, rec, Lr);
         float s, lo;
         if (meta_fp32) {
             s = *reinterpret_cast<const float*>(in + (rec.scale + 4u * g));
@@ -994,25 +1004,27 @@ static unsigned persistent_grid(uint32_t n_tiles) {
 }
 
 template <int BITS, int G, bool SR> struct LaunchQuantize {
-    static int run(const void* x, uint64_t n, void* out, const Rec& rec, uint32_t meta_fp32, hipStream_t st) {
+    static int run(const void* x, uint64_t n, void* out, const Rec& rec, uint32_t meta_fp32, uint32_t n_slices,
+                   uint64_t record_stride, hipStream_t st) {
         constexpr int EPL = kEplStream;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
         const uint32_t n_tiles = (n_lanes + 63) / 64;
         hipLaunchKernelGGL((k_quantize_pack_t<BITS, G / EPL, SR>), dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
-                           (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_fp32);
+                           (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_fp32, n_lanes / n_slices, record_stride);
         return launch_status();
     }
 };
 template <int BITS, int G, bool SR> struct LaunchUnpack {
-    static int run(const void* in, const Rec& rec, uint64_t n, void* out, uint32_t out_fp32, uint32_t meta_fp32, hipStream_t st) {
+    static int run(const PeerPtrs& records, uint32_t n_slices, const Rec& rec, uint64_t n, void* out, uint32_t out_fp32,
+                   uint32_t meta_fp32, hipStream_t st) {
         constexpr int EPL = kEplStream;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
         if (out_fp32)
             hipLaunchKernelGGL((k_unpack_dequant_t<BITS, G / EPL, SR, true>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
-                               (const uint8_t*)in, rec, n_lanes, (uint4*)out, meta_fp32);
+                               records, n_lanes / n_slices, rec, n_lanes, (uint4*)out, meta_fp32);
         else
             hipLaunchKernelGGL((k_unpack_dequant_t<BITS, G / EPL, SR, false>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
-                               (const uint8_t*)in, rec, n_lanes, (uint4*)out, meta_fp32);
+                               records, n_lanes / n_slices, rec, n_lanes, (uint4*)out, meta_fp32);
         return launch_status();
     }
 };
@@ -1117,27 +1129,56 @@ int fcv2_get_layout(uint64_t n, const fcv2_fmt_t* fmt, uint32_t align, fcv2_layo
 // Largest tensor the kernels index with 32-bit offsets: 2^31 elements (a 4 GiB bf16 tensor).
 static const uint64_t kMaxElems = 1ull << 31;
 
-int fcv2_quantize_pack(const void* x, uint64_t n, const fcv2_fmt_t* fmt, void* packed, void* stream) {
+// Slices of a two-step AllReduce payload: equal length, whole groups, whole 2048-element wave tiles.
+static int check_slices(uint64_t n, uint32_t n_slices, const fcv2_fmt_t* fmt, fcv2_layout_t* slice_layout) {
+    if (n_slices < 1 || n_slices > FCV2_MAX_PEERS || n == 0 || n % n_slices != 0) return FCV2_ERR_INVALID_ARG;
+    const uint64_t len = n / n_slices;
+    int rc = fcv2_get_layout(len, fmt, FCV2_TENSOR_ALIGN, slice_layout);
+    if (rc != FCV2_OK) return rc;
+    if (n_slices > 1 && len % 2048 != 0) return FCV2_ERR_INVALID_ARG;
+    if (n > kMaxElems) return FCV2_ERR_UNSUPPORTED;
+    return FCV2_OK;
+}
+
+int fcv2_quantize_pack_slices(const void* x, uint64_t n, uint32_t n_slices, const fcv2_fmt_t* fmt, void* packed,
+                              uint64_t record_stride, void* stream) {
     if (!x || !packed || !fmt) return FCV2_ERR_INVALID_ARG;
     fcv2_layout_t l;
-    int rc = fcv2_get_layout(n, fmt, FCV2_TENSOR_ALIGN, &l);
+    int rc = check_slices(n, n_slices, fmt, &l);
     if (rc != FCV2_OK) return rc;
-    if (n > kMaxElems) return FCV2_ERR_UNSUPPORTED;
+    if (n_slices > 1 && (record_stride < l.total_bytes || record_stride % FCV2_TENSOR_ALIGN != 0)) return FCV2_ERR_INVALID_ARG;
     if (!aligned16(x) || !aligned16(packed)) return FCV2_ERR_ALIGN;
-    return by_format<LaunchQuantize>(fmt, x, n, packed, rec_of(l),
-                                     (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0), (hipStream_t)stream);
+    return by_format<LaunchQuantize>(fmt, x, n, packed, rec_of(l), (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0), n_slices,
+                                     record_stride, (hipStream_t)stream);
+}
+
+int fcv2_quantize_pack(const void* x, uint64_t n, const fcv2_fmt_t* fmt, void* packed, void* stream) {
+    return fcv2_quantize_pack_slices(x, n, 1, fmt, packed, 0, stream);
+}
+
+int fcv2_unpack_dequant_slices(const void* const* records, uint32_t n_slices, uint64_t n, const fcv2_fmt_t* fmt, void* out,
+                               int out_dtype, void* stream) {
+    if (!records || !out || !fmt) return FCV2_ERR_INVALID_ARG;
+    if (out_dtype != FCV2_DT_BF16 && out_dtype != FCV2_DT_FP32) return FCV2_ERR_INVALID_ARG;
+    fcv2_layout_t l;
+    int rc = check_slices(n, n_slices, fmt, &l);
+    if (rc != FCV2_OK) return rc;
+    if (!aligned16(out)) return FCV2_ERR_ALIGN;
+    PeerPtrs pp;
+    for (uint32_t p = 0; p < FCV2_MAX_PEERS; ++p) {
+        const void* ptr = records[p < n_slices ? p : 0];
+        if (!ptr) return FCV2_ERR_INVALID_ARG;
+        if (!aligned16(ptr)) return FCV2_ERR_ALIGN;
+        pp.base[p] = (const uint8_t*)ptr;
+    }
+    return by_format<LaunchUnpack>(fmt, pp, n_slices, rec_of(l), n, out, (uint32_t)(out_dtype == FCV2_DT_FP32),
+                                   (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0), (hipStream_t)stream);
 }
 
 int fcv2_unpack_dequant(const void* packed, uint64_t n, const fcv2_fmt_t* fmt, void* out, int out_dtype, void* stream) {
-    if (!packed || !out || !fmt) return FCV2_ERR_INVALID_ARG;
-    if (out_dtype != FCV2_DT_BF16 && out_dtype != FCV2_DT_FP32) return FCV2_ERR_INVALID_ARG;
-    fcv2_layout_t l;
-    int rc = fcv2_get_layout(n, fmt, FCV2_TENSOR_ALIGN, &l);
-    if (rc != FCV2_OK) return rc;
-    if (n > kMaxElems) return FCV2_ERR_UNSUPPORTED;
-    if (!aligned16(packed) || !aligned16(out)) return FCV2_ERR_ALIGN;
-    return by_format<LaunchUnpack>(fmt, packed, rec_of(l), n, out, (uint32_t)(out_dtype == FCV2_DT_FP32),
-                                   (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0), (hipStream_t)stream);
+    const void* one[1] = {packed};
+    if (!packed) return FCV2_ERR_INVALID_ARG;
+    return fcv2_unpack_dequant_slices(one, 1, n, fmt, out, out_dtype, stream);
 }
 
 int fcv2_reduce_requant(const void* const* peers, int n_peers, uint64_t n, const fcv2_fmt_t* fmt_in, const fcv2_fmt_t* fmt_out,

@@ -65,6 +65,9 @@ def lib():
         L.fcv2_get_layout.argtypes = [C.c_uint64, fmtp, C.c_uint32, C.POINTER(_Layout)]
         L.fcv2_quantize_pack.argtypes = [vp, C.c_uint64, fmtp, vp, vp]
         L.fcv2_unpack_dequant.argtypes = [vp, C.c_uint64, fmtp, vp, C.c_int, vp]
+        L.fcv2_quantize_pack_slices.argtypes = [vp, C.c_uint64, C.c_uint32, fmtp, vp, C.c_uint64, vp]
+        L.fcv2_unpack_dequant_slices.argtypes = [C.POINTER(vp), C.c_uint32, C.c_uint64, fmtp, vp, C.c_int, vp]
+        L.fcv2_stream_copy.argtypes = [vp, vp, C.c_uint64, vp]
         L.fcv2_reduce_requant.argtypes = [C.POINTER(vp), C.c_int, C.c_uint64, fmtp, fmtp, vp, vp, vp]
         L.fcv2_dispatch_workspace_bytes.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_size_t)]
         L.fcv2_dispatch_quant.argtypes = [vp, vp, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, fmtp, vp, vp, vp,
@@ -131,6 +134,50 @@ def unpack_dequant(packed: torch.Tensor, n, bits, group, flags, out_dtype=torch.
                                      DT_FP32 if out_dtype == torch.float32 else DT_BF16, _stream()),
            "fcv2_unpack_dequant")
     return out
+
+
+def quantize_pack_slices(x: torch.Tensor, n_slices, bits, group, flags, out: torch.Tensor = None) -> torch.Tensor:
+    """Cut x into n_slices equal slices and pack each into a record of its own.  Returns a uint8 tensor
+    [n_slices, record_stride]; row j is the record of slice j."""
+    if x.dtype != torch.bfloat16:
+        raise Fcv2Error("x must be bfloat16")
+    n = x.numel()
+    if n_slices < 1 or n % n_slices:
+        raise Fcv2Error("n must be a multiple of n_slices")
+    L = get_layout(n // n_slices, bits, group, flags)
+    if out is None:
+        out = torch.zeros((n_slices, L.total_bytes), dtype=torch.uint8, device=x.device)
+    elif out.dtype != torch.uint8 or out.dim() != 2 or out.shape[0] != n_slices or out.shape[1] < L.total_bytes:
+        raise Fcv2Error("out must be a uint8 tensor [n_slices, >= total_bytes]")
+    _check(lib().fcv2_quantize_pack_slices(_dev(x, "x"), n, n_slices, C.byref(_Fmt(bits, group, flags)), _dev(out, "out"),
+                                           out.shape[1], _stream()), "fcv2_quantize_pack_slices")
+    return out
+
+
+def unpack_dequant_slices(records, n, bits, group, flags, out_dtype=torch.float32, out: torch.Tensor = None) -> torch.Tensor:
+    """records: list of packed uint8 device tensors, record j = slice j of the output of n elements."""
+    k = len(records)
+    if k < 1 or n % k:
+        raise Fcv2Error("n must be a multiple of the number of records")
+    L = get_layout(n // k, bits, group, flags)
+    for r in records:
+        if r.dtype != torch.uint8 or r.numel() < L.total_bytes:
+            raise Fcv2Error("every record must be a uint8 tensor of at least total_bytes")
+    if out is None:
+        out = torch.empty(n, dtype=out_dtype, device=records[0].device)
+    arr = (C.c_void_p * k)(*[_dev(r, "record").value for r in records])
+    _check(lib().fcv2_unpack_dequant_slices(arr, k, n, C.byref(_Fmt(bits, group, flags)), _dev(out, "out"),
+                                            DT_FP32 if out_dtype == torch.float32 else DT_BF16, _stream()),
+           "fcv2_unpack_dequant_slices")
+    return out
+
+
+def stream_copy(src: torch.Tensor, dst: torch.Tensor):
+    """Diagnostic: plain streaming copy of src into dst (same byte size, a multiple of 16)."""
+    nbytes = src.numel() * src.element_size()
+    if nbytes != dst.numel() * dst.element_size():
+        raise Fcv2Error("src and dst differ in size")
+    _check(lib().fcv2_stream_copy(_dev(src, "src"), _dev(dst, "dst"), nbytes, _stream()), "fcv2_stream_copy")
 
 
 def reduce_requant(peers, n, fmt_in, fmt_out=None, want_sum=False, out: torch.Tensor = None,

@@ -206,6 +206,77 @@ def test_reduce_requant_edge_cases():
         check_reduce(xs, 2, group, SR, f"edge g{group} b2")
 
 
+# ---- slices and the whole two-step AllReduce on one GPU (Sections 3.1, 3.4) ----------------------------------
+
+@pytest.mark.parametrize("bits,group", [(2, 32), (3, 128), (5, 64), (8, 256)])
+def test_slices_match_per_slice_records(bits, group):
+    R, n = 4, 4 * 2048 * 3
+    x = W.tensor(2, 0, rows=1, cols=n).reshape(-1)
+    L = O.get_layout(n // R, bits, group, SR)
+    got = fcv2.quantize_pack_slices(to_dev_bf16(x), R, bits, group, SR)
+    assert got.shape == (R, L.total_bytes)
+    recs_o = [O.quantize_pack(x[j * n // R:(j + 1) * n // R], bits, group, SR) for j in range(R)]
+    for j in range(R):
+        assert_packed_equal(got[j].cpu().numpy(), recs_o[j], L, SR, f"slice {j} b{bits} g{group}")
+    want = np.concatenate([O.unpack_dequant(r, n // R, bits, group, SR) for r in recs_o])
+    for dt, view in ((torch.float32, np.uint32), (torch.bfloat16, np.uint16)):
+        out = fcv2.unpack_dequant_slices([torch.from_numpy(r).to(DEV) for r in recs_o], n, bits, group, SR, dt)
+        if dt == torch.float32:
+            assert np.array_equal(out.cpu().numpy().view(view), want.view(view))
+        else:
+            wb = np.concatenate([O.unpack_dequant(r, n // R, bits, group, SR, O.DT_BF16) for r in recs_o])
+            assert np.array_equal(out.view(torch.int16).cpu().numpy().view(view), wb)
+
+
+def test_slice_arguments_are_checked():
+    x = to_dev_bf16(W.tensor(2, 0, rows=1, cols=8192).reshape(-1))
+    with pytest.raises(fcv2.Fcv2Error):
+        fcv2.quantize_pack_slices(x, 3, 4, 128, SR)  # 8192 not a multiple of 3
+    with pytest.raises(fcv2.Fcv2Error):
+        fcv2.quantize_pack_slices(x, 8, 4, 128, SR)  # slices of 1024 elements: not whole wave tiles
+    with pytest.raises(fcv2.Fcv2Error):
+        fcv2.quantize_pack_slices(x, 32, 4, 128, SR)  # more than 16 slices
+
+
+@pytest.mark.parametrize("bits", [2, 3, 4, 6, 8])
+def test_two_step_allreduce_on_one_gpu(bits):
+    """R simulated ranks: every rank packs its payload as R slices, rank j reduces the R copies of slice j, every
+    rank unpacks the R reduced slices.  The GPU pipeline equals the oracle's bit for bit, and the result stays within
+    the quantization error bound of the exact sum."""
+    R, n, group = 8, 8 * 2048 * 2, 128
+    fmt = (bits, group, SR)
+    xs = [W.tensor(2, r, rows=1, cols=n).reshape(-1) for r in range(R)]
+    m = n // R
+    L = O.get_layout(m, *fmt)
+    # oracle pipeline
+    send_o = [[O.quantize_pack(x[j * m:(j + 1) * m], *fmt) for j in range(R)] for x in xs]
+    red_o = [O.reduce_requant([send_o[r][j] for r in range(R)], m, fmt) for j in range(R)]
+    out_o = np.concatenate([O.unpack_dequant(red_o[j], m, *fmt, O.DT_BF16) for j in range(R)])
+    # GPU pipeline, through the C ABI
+    send_g = [fcv2.quantize_pack_slices(to_dev_bf16(x), R, *fmt) for x in xs]
+    red_g = [fcv2.reduce_requant([send_g[r][j] for r in range(R)], m, fmt) for j in range(R)]
+    out_g = fcv2.unpack_dequant_slices(red_g, n, *fmt, torch.bfloat16)
+    for j in range(R):
+        assert_packed_equal(red_g[j].cpu().numpy(), red_o[j], L, SR, f"reduced slice {j}")
+    assert np.array_equal(out_g.view(torch.int16).cpu().numpy().view(np.uint16), out_o)
+    # against the exact sum: every term is off by at most half a step of its group (spikes are exact), the sum is
+    # rounded to bf16, and the second quantization adds half a step of the output group
+    exact = np.sum([W.bf16_bits_to_f32(x).astype(np.float64) for x in xs], axis=0)
+    got = W.bf16_bits_to_f32(out_o).astype(np.float64)
+
+    def steps(rec, layout):
+        sc = W.bf16_bits_to_f32(rec[layout.off_scale:layout.off_scale + 2 * layout.n_groups].view(np.uint16))
+        return np.repeat(sc.astype(np.float64), group)
+
+    bound = np.zeros(n)
+    for j in range(R):
+        b = sum(steps(send_o[r][j], L) for r in range(R)) * (0.5 + 2.0 ** -7)
+        s_exact = np.abs(exact[j * m:(j + 1) * m]) + b
+        b = b + s_exact * 2.0 ** -8 + steps(red_o[j], L) * (0.5 + 2.0 ** -7) + s_exact * 2.0 ** -8
+        bound[j * m:(j + 1) * m] = b
+    assert np.all(np.abs(got - exact) <= bound)
+
+
 # ---- dispatch_quant -------------------------------------------------------------------------------------------------
 
 def check_dispatch(x, ids, E, bits, group, flags, what):
