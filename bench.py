@@ -227,6 +227,18 @@ def main():
         del bufs, x3
         torch.cuda.empty_cache()
 
+    # ---- quality proxy: signal-to-quantization-noise of plain RTN against spike reserving (direction of Tables 3, 7, 8) --
+    quality = {}
+    if not args.no_sweep:
+        xf = xs[0].float()
+        for b in (2, 3, 4, 5, 6, 8):
+            row = {}
+            for name, fl in (("rtn", 0), ("spike_reserving", SR)):
+                v = fcv2.unpack_dequant(fcv2.quantize_pack(xs[0], b, group, fl), n, b, group, fl, torch.float32)
+                row[name + "_sqnr_db"] = round(float(10 * torch.log10(xf.pow(2).sum() / (v - xf).pow(2).sum())), 2)
+            quality[str(b)] = row
+        del xf
+
     # ---- one rank's share of a whole two-step AllReduce over 8 ranks on the headline payload ------------------------
     two_step = None
     if not args.no_sweep:
@@ -238,10 +250,19 @@ def main():
         out_t = torch.empty(n, dtype=torch.bfloat16, device=dev)
         sbuf = torch.zeros_like(send[0])
 
+        import ctypes as C
+        lib = fcv2.lib()
+        st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        f3 = fcv2._Fmt(3, group, SR)
+        arr_mine = [(C.c_void_p * R)(*[t.data_ptr() for t in mine[j]]) for j in range(R)]
+        arr_red = (C.c_void_p * R)(*[t.data_ptr() for t in red])
+
         def rank_step(i):
-            fcv2.quantize_pack_slices(xs[i % R], R, 3, group, SR, out=sbuf)              # pack my payload as 8 slices
-            fcv2.reduce_requant(mine[i % R], m, (3, group, SR), out=red[i % R])          # reduce my slice over 8 peers
-            fcv2.unpack_dequant_slices(red, n, 3, group, SR, torch.bfloat16, out=out_t)  # unpack the 8 reduced slices
+            j = i % R
+            lib.fcv2_quantize_pack_slices(C.c_void_p(xs[j].data_ptr()), n, R, C.byref(f3), C.c_void_p(sbuf.data_ptr()),
+                                          sbuf.shape[1], st)                               # pack my payload as 8 slices
+            lib.fcv2_reduce_requant(arr_mine[j], R, m, C.byref(f3), C.byref(f3), C.c_void_p(red[j].data_ptr()), None, st)
+            lib.fcv2_unpack_dequant_slices(arr_red, R, n, C.byref(f3), C.c_void_p(out_t.data_ptr()), fcv2.DT_BF16, st)
 
         ms_ts = timed(rank_step, max(20, args.steps // 2), 3)
         P1 = packed_bytes(m, 3, group)
@@ -329,7 +350,7 @@ def main():
         "warm_cache_gbs": round(total_bytes / (ms_warm * 1e-3) / 1e9, 1),
         "copy_ceiling_gbs": round(copy_gbs, 1),
         "kernels": kernels, "roofline": roofline, "alu_roofline": alu, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
-        "two_step_allreduce_rank_share": two_step, "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
+        "quality_proxy_sqnr_g128": quality, "two_step_allreduce_rank_share": two_step, "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
     }
     print(json.dumps(out))
 
