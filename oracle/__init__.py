@@ -12,6 +12,7 @@ from . import build as _build
 
 F_SPIKE = 1
 F_META_FP32 = 2
+F_META_INT = 4
 DT_BF16 = 0
 DT_FP32 = 1
 ABSENT = 2**64 - 1
@@ -64,6 +65,11 @@ def lib():
         L.orc_reduce_requant.argtypes = [C.POINTER(u8p), C.c_int, C.c_uint64, fmtp, fmtp, C.c_uint32, u8p, f32p]
         L.orc_dispatch_quant.argtypes = [u16p, i32p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, fmtp, u8p,
                                          i32p, i32p]
+        L.orc_scale_int.argtypes = [C.c_float]
+        L.orc_scale_int.restype = C.c_int
+        L.orc_scale_of_int.argtypes = [C.c_int]
+        L.orc_scale_of_int.restype = C.c_float
+        L.orc_meta_int.argtypes = [C.c_float, C.c_float, C.c_uint32, C.POINTER(C.c_int8), u8p, f32p, f32p]
         _lib = L
     return _lib
 
@@ -93,6 +99,22 @@ def key(u16) -> int:
 
 def bf16_rne(v: float) -> int:
     return int(lib().orc_bf16_rne(float(v)))
+
+
+def scale_int(scale: float) -> int:
+    """Eq. 1 with theta = 10, clamped to a signed byte."""
+    return int(lib().orc_scale_int(float(scale)))
+
+
+def scale_of_int(k: int):
+    return np.float32(lib().orc_scale_of_int(int(k)))
+
+
+def meta_int(lo: float, hi: float, bits: int):
+    """Integer metadata of a group whose values to quantize span [lo, hi]: (scale_int, zero_int, scale, offset)."""
+    k, z, s, zf = C.c_int8(), C.c_uint8(), C.c_float(), C.c_float()
+    _chk(lib().orc_meta_int(float(lo), float(hi), bits, C.byref(k), C.byref(z), C.byref(s), C.byref(zf)), "meta_int")
+    return int(k.value), int(z.value), np.float32(s.value), np.float32(zf.value)
 
 
 def quantize_group(x_u16, bits, flags):

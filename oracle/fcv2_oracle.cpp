@@ -14,7 +14,12 @@
 //     qmax*scale still covers the range; the encoder quantizes with the stored scale; zero = lo
 //     (a float offset, exact in bf16 because it is an input value);
 //   * widest plane holds the most-significant bits ("first 4 bits" of Fig. 3); inside a plane byte
-//     the element with the lowest index sits in the least-significant bits.
+//     the element with the lowest index sits in the least-significant bits;
+//   * integer metadata (Eq. 1, Table 4 second row; flag ORC_F_META_INT): one signed byte
+//     scale_int = round(log2(scale) * 10) clamped to [-128, 127], decoded as 2^(scale_int / 10) rounded to
+//     fp32; one unsigned byte zero = the usual integer zero-point round(-lo / scale) over a range widened to
+//     contain 0 (so it always fits the byte), decoded as the offset -(zero * scale); the encoder quantizes
+//     with the decoded scale and offset, codes are clamped to [0, qmax].
 #include "fcv2_oracle.h"
 
 #include <cmath>
@@ -53,7 +58,8 @@ int plane_widths(uint32_t bits, int w[3]) {
 
 bool fmt_ok(const orc_fmt* f) {
     return f && f->bits >= 2 && f->bits <= 8 && f->group >= 3 && f->group <= 256 &&
-           (f->flags & ~(ORC_F_SPIKE | ORC_F_META_FP32)) == 0;
+           (f->flags & ~(ORC_F_SPIKE | ORC_F_META_FP32 | ORC_F_META_INT)) == 0 &&
+           (f->flags & (ORC_F_META_FP32 | ORC_F_META_INT)) != (ORC_F_META_FP32 | ORC_F_META_INT);
 }
 
 uint64_t plane_offset(const orc_layout& L, int width) {
@@ -97,7 +103,7 @@ int orc_get_layout(uint64_t n, const orc_fmt* fmt, uint32_t align, orc_layout* L
         if (w[p] == 1) L->off_plane1 = off;
         off += n * (uint64_t)w[p] / 8;
     }
-    uint64_t meta_elem = (fmt->flags & ORC_F_META_FP32) ? 4 : 2;
+    uint64_t meta_elem = (fmt->flags & ORC_F_META_FP32) ? 4 : (fmt->flags & ORC_F_META_INT) ? 1 : 2;
     off = round_up(off, align);
     L->off_scale = off;
     off += L->n_groups * meta_elem;
@@ -116,9 +122,44 @@ int orc_get_layout(uint64_t n, const orc_fmt* fmt, uint32_t align, orc_layout* L
     return ORC_OK;
 }
 
-// One group.  Section 3.1 (asymmetric RTN per group) and Section 3.3 (spike reserving).
-int orc_quantize_group(const uint16_t* x, const orc_fmt* fmt, uint8_t* codes, float* scale, float* zero,
-                       uint16_t* spike_val, uint8_t* spike_idx) {
+// Eq. 1 with theta = 10: the scale as one signed byte.  log2(0) = -inf lands on the lowest code, and so
+// does a NaN.
+int orc_scale_int(float scale) {
+    if (!(scale > 0.0f)) return -128;
+    const double t = std::nearbyint(std::log2((double)scale) * 10.0);
+    return (int)std::fmin(std::fmax(t, -128.0), 127.0);
+}
+
+// The scale a receiver reconstructs from the byte: 2^(scale_int / theta), as an fp32 value.
+float orc_scale_of_int(int scale_int) { return (float)std::exp2((double)scale_int / 10.0); }
+
+// Integer metadata of one group from the range [lo, hi] that is to be quantized with `bits` bits: the range is
+// widened to contain 0, the scale goes through Eq. 1, the zero-point is the rounded quotient -lo / scale (one
+// unsigned byte).  s and zf are what the receiver reconstructs: scale and offset.
+int orc_meta_int(float lo, float hi, uint32_t bits, int8_t* scale_int, uint8_t* zero_int, float* s, float* zf) {
+    if (bits < 2 || bits > 8 || !scale_int || !zero_int || !s || !zf) return ORC_ERR_ARG;
+    const int qmax = (1 << bits) - 1;
+    const float lo0 = (lo < 0.0f) ? lo : 0.0f;
+    const float hi0 = (hi > 0.0f) ? hi : 0.0f;
+    const float s32 = (hi0 - lo0) / (float)qmax;
+    const int k = orc_scale_int(s32);
+    const float sd = orc_scale_of_int(k);
+    const float inv = 1.0f / sd;
+    const float tz = (-lo0) * inv;
+    const int z = (tz >= 0.0f) ? (int)std::fmin(std::rint(tz), 255.0f) : 0;
+    *scale_int = (int8_t)k;
+    *zero_int = (uint8_t)z;
+    *s = sd;
+    *zf = -((float)z * sd);
+    return ORC_OK;
+}
+
+}  // extern "C"
+
+// One group.  Section 3.1 (asymmetric RTN per group) and Section 3.3 (spike reserving).  meta_int[2] receives the
+// two metadata bytes when the format stores integer metadata.
+static int quantize_group(const uint16_t* x, const orc_fmt* fmt, uint8_t* codes, float* scale, float* zero,
+                          uint16_t* spike_val, uint8_t* spike_idx, uint8_t* meta_int) {
     if (!fmt_ok(fmt) || !x || !codes || !scale || !zero) return ORC_ERR_ARG;
     const int G = (int)fmt->group;
     const int qmax = (1 << fmt->bits) - 1;
@@ -147,16 +188,26 @@ int orc_quantize_group(const uint16_t* x, const orc_fmt* fmt, uint8_t* codes, fl
         if (ilo < 0 || orc_key(x[i]) < orc_key(x[ilo])) ilo = i;
         if (ihi < 0 || orc_key(x[i]) > orc_key(x[ihi])) ihi = i;
     }
-    const float lo = bf16_to_f32(x[ilo]);
+    float lo = bf16_to_f32(x[ilo]);
     const float hi = bf16_to_f32(x[ihi]);
-    const float s32 = (hi - lo) / (float)qmax;
     float s;
-    if (!(s32 >= 0x1p-64f)) {
-        s = 1.0f;  // constant rest, vanishing range, or NaN
-    } else if (fmt->flags & ORC_F_META_FP32) {
-        s = s32;
+    if (fmt->flags & ORC_F_META_INT) {
+        int8_t k;
+        uint8_t z;
+        float zf;
+        orc_meta_int(lo, hi, fmt->bits, &k, &z, &s, &zf);
+        lo = zf;  // the offset the receiver will use
+        meta_int[0] = (uint8_t)k;
+        meta_int[1] = z;
     } else {
-        s = bits_to_f32((f32_to_bits(s32) + 0xFFFFu) & 0xFFFF0000u);  // bf16, rounded up
+        const float s32 = (hi - lo) / (float)qmax;
+        if (!(s32 >= 0x1p-64f)) {
+            s = 1.0f;  // constant rest, vanishing range, or NaN
+        } else if (fmt->flags & ORC_F_META_FP32) {
+            s = s32;
+        } else {
+            s = bits_to_f32((f32_to_bits(s32) + 0xFFFFu) & 0xFFFF0000u);  // bf16, rounded up
+        }
     }
     *scale = s;
     *zero = lo;
@@ -172,6 +223,14 @@ int orc_quantize_group(const uint16_t* x, const orc_fmt* fmt, uint8_t* codes, fl
         codes[i] = (uint8_t)(int)r;
     }
     return ORC_OK;
+}
+
+extern "C" {
+
+int orc_quantize_group(const uint16_t* x, const orc_fmt* fmt, uint8_t* codes, float* scale, float* zero,
+                       uint16_t* spike_val, uint8_t* spike_idx) {
+    uint8_t meta_int[2];
+    return quantize_group(x, fmt, codes, scale, zero, spike_val, spike_idx, meta_int);
 }
 
 // Bit splitting (Section 3.2): every plane is its own contiguous section.
@@ -227,9 +286,13 @@ int orc_quantize_pack(const uint16_t* x, uint64_t n, const orc_fmt* fmt, uint32_
         float s, z;
         uint16_t sv[2] = {0, 0};
         uint8_t si[2] = {0, 0};
-        int rc = orc_quantize_group(x + g * G, fmt, codes.data() + g * G, &s, &z, sv, si);
+        uint8_t mi[2] = {0, 0};
+        int rc = quantize_group(x + g * G, fmt, codes.data() + g * G, &s, &z, sv, si, mi);
         if (rc != ORC_OK) return rc;
-        if (fmt->flags & ORC_F_META_FP32) {
+        if (fmt->flags & ORC_F_META_INT) {
+            packed[L.off_scale + g] = mi[0];
+            packed[L.off_zero + g] = mi[1];
+        } else if (fmt->flags & ORC_F_META_FP32) {
             std::memcpy(packed + L.off_scale + 4 * g, &s, 4);
             std::memcpy(packed + L.off_zero + 4 * g, &z, 4);
         } else {
@@ -259,7 +322,10 @@ static int decode_f32(const uint8_t* packed, uint64_t n, const orc_fmt* fmt, uin
     const uint32_t G = fmt->group;
     for (uint64_t g = 0; g < L.n_groups; ++g) {
         float s, z;
-        if (fmt->flags & ORC_F_META_FP32) {
+        if (fmt->flags & ORC_F_META_INT) {
+            s = orc_scale_of_int((int)(int8_t)packed[L.off_scale + g]);
+            z = -((float)packed[L.off_zero + g] * s);
+        } else if (fmt->flags & ORC_F_META_FP32) {
             std::memcpy(&s, packed + L.off_scale + 4 * g, 4);
             std::memcpy(&z, packed + L.off_zero + 4 * g, 4);
         } else {

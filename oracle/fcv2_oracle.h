@@ -13,6 +13,8 @@
  *   - spike reserving: group min and max kept in float form with their
  *     in-group indices, the rest quantized over the shrunk range            (Section 3.3, Fig. 5)
  *   - metadata section sizes                                               (Section 3.3, Table 4)
+ *   - integer metadata: the scale as one byte, scale_int = round(log2(scale) * 10),
+ *     and a one-byte zero                                                  (Section 3.3, Eq. 1, Table 4)
  *   - local dequantize-sum-requantize step of the two-step AllReduce        (Sections 3.1, 3.4)
  *   - dispatch-only quantization for MoE All2All                            (Section 3.1, 4.4)
  *
@@ -34,7 +36,7 @@ extern "C" {
 #endif
 
 enum { ORC_OK = 0, ORC_ERR_ARG = -1 };
-enum { ORC_F_SPIKE = 1u, ORC_F_META_FP32 = 2u };
+enum { ORC_F_SPIKE = 1u, ORC_F_META_FP32 = 2u, ORC_F_META_INT = 4u };
 enum { ORC_DT_BF16 = 0, ORC_DT_FP32 = 1 };
 
 typedef struct {
@@ -63,6 +65,13 @@ uint32_t orc_key(uint16_t bf16_bits);
  * quantizer separately from the wire format. */
 int orc_quantize_group(const uint16_t* x, const orc_fmt* fmt, uint8_t* codes, float* scale, float* zero,
                        uint16_t* spike_val, uint8_t* spike_idx);
+
+/* Integer metadata (ORC_F_META_INT).  Eq. 1 with theta = 10, clamped to a signed byte; its inverse
+ * 2^(scale_int / 10) as an fp32 value; and both bytes of a group whose values to quantize span [lo, hi],
+ * together with the scale s and the offset zf = -(zero_int * s) that a receiver reconstructs from them. */
+int orc_scale_int(float scale);
+float orc_scale_of_int(int scale_int);
+int orc_meta_int(float lo, float hi, uint32_t bits, int8_t* scale_int, uint8_t* zero_int, float* s, float* zf);
 
 /* Split n codes into the planes of `bits` and back (planes laid out with orc_get_layout(n, fmt, align)). */
 int orc_split_pack(const uint8_t* codes, uint64_t n, const orc_fmt* fmt, uint32_t align, uint8_t* packed);

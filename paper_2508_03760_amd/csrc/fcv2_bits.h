@@ -15,6 +15,16 @@
 #define FCV2_HD inline
 #endif
 
+// Tables and the functions that index them: device-only inside the HIP translation unit, plain host code in
+// the CPU test build.
+#if defined(__HIPCC__)
+#define FCV2_TABLE static __device__ const
+#define FCV2_D __device__ __forceinline__
+#else
+#define FCV2_TABLE static const
+#define FCV2_D inline
+#endif
+
 // Keeps the compiler from merging a chain of shift-or steps into one 32-bit multiply (quarter rate on CDNA).
 #if defined(__HIP_DEVICE_COMPILE__)
 #define FCV2_KEEP(v) asm volatile("" : "+v"(v))
@@ -57,6 +67,63 @@ template <int QMAX> FCV2_HD float div_by_qmax(float d) {
     const float r = fmaf(-(float)QMAX, q0, d);
     const float q1 = fmaf(r, y, q0);
     return (d < INFINITY) ? q1 : d;
+}
+
+// ---- integer metadata (Section 3.3, Eq. 1: scale_int = round(log2(scale) * 10), one signed byte) -------------
+// kPow10th[j + 1] = 2^(j/10) rounded to fp32 for j = -1..10.  kThr10th[j] = 2^((j - 1/2)/10) rounded UP to fp32 for
+// j = 0..10: a scale s has round(log2(s) * 10) >= 10e + j exactly when s >= 2^e * kThr10th[j] (the true thresholds
+// are irrational, so rounding them up to the next fp32 changes no decision).
+FCV2_TABLE float kPow10th[12] = {0x1.ddb680p-1f, 0x1.000000p+0f, 0x1.125fbep+0f, 0x1.261118p+0f, 0x1.3b2c48p+0f, 0x1.51cb46p+0f,
+                                 0x1.6a09e6p+0f, 0x1.840600p+0f, 0x1.9fdf8cp+0f, 0x1.bdb8cep+0f, 0x1.ddb680p+0f, 0x1.000000p+1f};
+FCV2_TABLE float kThr10th[11] = {0x1.ee8f36p-1f, 0x1.090720p+0f, 0x1.1c0cc0p+0f, 0x1.306fe2p+0f, 0x1.46499cp+0f, 0x1.5db4d2p+0f,
+                                 0x1.76ce52p+0f, 0x1.91b502p+0f, 0x1.ae89fap+0f, 0x1.cd70b4p+0f, 0x1.ee8f36p+0f};
+
+// k = 10e + j with 0 <= j <= 9, for -128 <= k <= 127.
+FCV2_D void split_tenths(int k, int& e, int& j) {
+    const uint32_t u = (uint32_t)(k + 130);
+    const uint32_t q = (u * 205u) >> 11;  // u / 10 for u < 1029
+    e = (int)q - 13;
+    j = (int)(u - 10u * q);
+}
+
+// The scale a receiver reconstructs from the byte: 2^(k/10) as an fp32 value (the table entry scaled by an exact
+// power of two).
+FCV2_D float scale_of_int(int k) {
+    int e, j;
+    split_tenths(k, e, j);
+    return ldexpf(kPow10th[j + 1], e);
+}
+
+// round(log2(s) * 10) to within 1 from the bit pattern alone: exponent + significand fraction is a piecewise-linear
+// log2 that is low by at most 0.0861; centring that error leaves |10 * error| < 0.44, so the rounded estimate is
+// at most one off.
+FCV2_D int scale_int_estimate(float s) {
+    uint32_t bits;
+    __builtin_memcpy(&bits, &s, 4);
+    const float t = (float)((int32_t)bits - 0x3F800000) * (10.0f / 8388608.0f) + 0.43f;
+    return (int)rintf(fminf(fmaxf(t, -128.0f), 127.0f));
+}
+
+struct ScaleInt {
+    int k;    // Eq. 1, clamped to a signed byte
+    float s;  // 2^(k/10)
+};
+
+// Eq. 1 without a logarithm: the estimate is corrected by comparing s with the two thresholds around it.
+// Zero, negative and NaN inputs give the lowest code.
+FCV2_D ScaleInt scale_int_of(float s) {
+    int k0 = (s > 0.0f) ? scale_int_estimate(s) : -128;
+    int e, j;
+    split_tenths(k0, e, j);
+    const float below = ldexpf(kThr10th[j], e), above = ldexpf(kThr10th[j + 1], e);
+    int d = 0;
+    if (s >= above) d = 1;
+    if (s < below) d = -1;
+    if (k0 + d > 127 || k0 + d < -128) d = 0;
+    ScaleInt r;
+    r.k = k0 + d;
+    r.s = ldexpf(kPow10th[j + 1 + d], e);
+    return r;
 }
 
 // ---- codes (one per byte) -> planes ---------------------------------------------------------------------------

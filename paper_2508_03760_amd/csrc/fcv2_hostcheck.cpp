@@ -90,6 +90,20 @@ uint64_t hc_div_mismatches(int qmax, uint32_t first_bits, uint32_t count) {
     return ~0ull;
 }
 
+// Integer scale (Eq. 1) of `count` fp32 bit patterns starting at first_bits: k[i] and the bits of 2^(k/10).
+void hc_scale_int_of(uint32_t first_bits, uint32_t count, int8_t* k, uint32_t* s_bits) {
+    for (uint32_t i = 0; i < count; ++i) {
+        const uint32_t b = first_bits + i;
+        float f;
+        memcpy(&f, &b, 4);
+        const ScaleInt r = scale_int_of(f);
+        k[i] = (int8_t)r.k;
+        memcpy(&s_bits[i], &r.s, 4);
+    }
+}
+int hc_scale_int_estimate(float s) { return scale_int_estimate(s); }
+float hc_scale_of_int(int k) { return scale_of_int(k); }
+
 uint32_t hc_key_of_bf16(uint32_t u) { return key_of_bf16(u); }
 uint32_t hc_bf16_of_key(uint32_t k) { return bf16_of_key(k); }
 uint32_t hc_bf16_rne_bits(uint32_t u) { return bf16_rne_bits(u); }

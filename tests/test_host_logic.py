@@ -31,6 +31,12 @@ def hc():
     for f in ("hc_key_of_bf16", "hc_bf16_of_key", "hc_bf16_rne_bits", "hc_bf16_round_up_bits"):
         getattr(L, f).restype = C.c_uint32
         getattr(L, f).argtypes = [C.c_uint32]
+    L.hc_scale_int_of.restype = None
+    L.hc_scale_int_of.argtypes = [C.c_uint32, C.c_uint32, C.POINTER(C.c_int8), C.POINTER(C.c_uint32)]
+    L.hc_scale_int_estimate.restype = C.c_int
+    L.hc_scale_int_estimate.argtypes = [C.c_float]
+    L.hc_scale_of_int.restype = C.c_float
+    L.hc_scale_of_int.argtypes = [C.c_int]
     return L
 
 
@@ -156,3 +162,44 @@ def test_short_division_is_ieee_division(hc, qmax):
     assert hc.hc_div_mismatches(qmax, 0x7F000000, 0x00800001) == 0  # up to and including +inf
     assert hc.hc_div_mismatches(qmax, 0x00000000, 1 << 20) == 0
     assert hc.hc_div_mismatches(qmax, 0x00800000, 1 << 22) == 0
+
+
+# ---- integer scale (Eq. 1) as the kernels compute it: table thresholds instead of a logarithm -------------------------
+
+def _scale_int_block(hc, first_bits, count):
+    k = np.zeros(count, np.int8)
+    sb = np.zeros(count, np.uint32)
+    hc.hc_scale_int_of(first_bits, count, k.ctypes.data_as(C.POINTER(C.c_int8)), sb.ctypes.data_as(C.POINTER(C.c_uint32)))
+    return k, sb.view(np.float32)
+
+
+@pytest.mark.parametrize("exponent", [-14, -13, -7, -1, 0, 1, 5, 12, 13])
+def test_scale_int_every_significand(hc, exponent):
+    """Eq. 1 for every fp32 significand of a binade against float64 log2; the decoded scale is 2^(k/10)."""
+    first = (127 + exponent) << 23
+    k, s = _scale_int_block(hc, first, 1 << 23)
+    x = (np.arange(1 << 23, dtype=np.uint32) + np.uint32(first)).view(np.float32).astype(np.float64)
+    t = np.log2(x) * 10.0
+    want = np.clip(np.rint(t), -128, 127)
+    far = np.abs(t - np.floor(t) - 0.5) > 1e-9  # float64 log2 decides everything that is not within 1e-9 of a tie
+    assert far.sum() >= (1 << 23) - 40
+    assert np.array_equal(k[far].astype(np.float64), want[far])
+    assert np.all(np.abs(k.astype(np.float64) - want) <= 1)
+    assert np.array_equal(s, np.exp2(k.astype(np.float64) / 10.0).astype(np.float32))
+
+
+def test_scale_int_estimate_is_within_one(hc):
+    rng = np.random.default_rng(5)
+    for x in np.exp2(rng.uniform(-20, 20, 20000)).astype(np.float32):
+        exact = int(np.clip(np.rint(np.log2(np.float64(x)) * 10), -128, 127))
+        assert abs(hc.hc_scale_int_estimate(float(x)) - exact) <= 1
+
+
+def test_scale_int_ends_and_specials(hc):
+    for bits, want in ((0x00000000, -128), (0x00000001, -128), (0x007FFFFF, -128), (0x80000000, -128), (0xBF800000, -128),
+                       (0x7FC00000, -128), (0x7F800000, 127), (0x7F7FFFFF, 127), (0x3F800000, 0), (0x40000000, 10)):
+        k, s = _scale_int_block(hc, bits, 1)
+        assert int(k[0]) == want, hex(bits)
+        assert s[0] == np.float32(2.0 ** (want / 10.0))
+    for kk in range(-128, 128):
+        assert np.float32(hc.hc_scale_of_int(kk)) == np.float32(np.exp2(np.float64(kk) / 10.0))

@@ -16,6 +16,7 @@ from paper_2508_03760_amd import workloads as W
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 SR = O.F_SPIKE
 F32 = O.F_META_FP32
+INT = O.F_META_INT
 
 
 def bf(x):
@@ -368,6 +369,197 @@ def test_reduce_requant_different_output_format():
     peers = [O.quantize_pack(x, *fin) for x in xs]
     out, s = O.reduce_requant(peers, n, fin, fout, want_sum=True)
     assert np.array_equal(out, O.quantize_pack(W.f32_to_bf16_bits(s), *fout))
+
+
+# ---- integer metadata (Section 3.3, Eq. 1, second row of Table 4) ---------------------------------------------
+
+def test_table4_footprint_with_integer_scales():
+    """Second row of Table 4: one-byte scale and zero (256 B for 128 groups), bf16 spike values + byte indices
+    (768 B), 1024 B of metadata, 2048 B in all."""
+    rows = {}
+    for line in open(os.path.join(GOLD, "table4_footprint.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, *v = line.split()
+        rows[k] = list(map(int, v))
+    data, quant, sz, spikes, meta, total = rows["scale_int"]
+    L = O.get_layout(4096, 2, 32, SR | INT, align=1)
+    assert L.off_scale == quant
+    assert L.off_zero - L.off_scale == sz // 2 and L.off_spike_val - L.off_scale == sz
+    assert L.total_bytes - L.off_spike_val == spikes
+    assert L.total_bytes - L.off_scale == meta
+    assert L.total_bytes == total
+    assert total == rows["scale"][5] * 4 // 5  # "reduce the memory footprint by 20 %"
+    with pytest.raises(ValueError):
+        O.get_layout(4096, 2, 32, SR | INT | F32)  # one precision of the metadata at a time
+
+
+def _exact_pow2_tenths(k):
+    """2^(k/10) to 60 digits."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 60
+    return (Decimal(k) / 10 * Decimal(2).ln()).exp()
+
+
+def test_scale_int_is_eq1():
+    """Eq. 1 with theta = 10 on closed forms: powers of two, the tenth-octave points themselves, the clamps of a
+    signed byte, monotonicity, and the decision points 2^((k + 1/2)/10) located with 60-digit arithmetic."""
+    from decimal import Decimal
+    for m in range(-12, 13):
+        assert O.scale_int(2.0 ** m) == 10 * m
+    assert O.scale_int(0.0) == -128 and O.scale_int(1e-30) == -128 and O.scale_int(float("nan")) == -128
+    assert O.scale_int(1e30) == 127 and O.scale_int(float("inf")) == 127
+    assert O.scale_int(3.0) == 16 and O.scale_int(0.1) == -33 and O.scale_int(1000.0) == 100  # 15.85, -33.2, 99.66
+    for k in range(-128, 128):
+        assert O.scale_int(float(np.float32(float(_exact_pow2_tenths(k))))) == k
+    xs = np.exp2(np.linspace(-14, 14, 5001)).astype(np.float32)
+    ks = [O.scale_int(float(x)) for x in xs]
+    assert all(a <= b for a, b in zip(ks, ks[1:]))
+    for k in range(-127, 127, 7):
+        from decimal import getcontext
+        getcontext().prec = 60
+        thr = ((Decimal(2 * k + 1) / 20) * Decimal(2).ln()).exp()  # 2^((k + 1/2)/10): above it the code is k + 1
+        up = np.float32(float(thr))
+        if Decimal(float(up)) < thr:
+            up = np.nextafter(up, np.float32(np.inf))
+        dn = np.nextafter(up, np.float32(-np.inf))
+        assert Decimal(float(dn)) < thr < Decimal(float(up))
+        assert O.scale_int(float(up)) == k + 1 and O.scale_int(float(dn)) == k
+
+
+def test_scale_of_int_is_the_rounded_power():
+    """The receiver's scale is 2^(scale_int/10) correctly rounded to fp32 (checked with 60-digit arithmetic);
+    it inverts Eq. 1 and stays within 2^(1/20) of any scale that maps to the same byte."""
+    from decimal import Decimal
+    for k in range(-128, 128):
+        got = O.scale_of_int(k)
+        exact = _exact_pow2_tenths(k)
+        err = abs(Decimal(float(got)) - exact)
+        for other in (np.nextafter(got, np.float32(np.inf)), np.nextafter(got, np.float32(-np.inf))):
+            assert err < abs(Decimal(float(other)) - exact)
+        assert O.scale_int(float(got)) == k
+        if k % 10 == 0:
+            assert float(got) == 2.0 ** (k // 10)
+    rng = np.random.default_rng(3)
+    for s in np.exp2(rng.uniform(-12.7, 12.6, 2000)).astype(np.float32):
+        r = float(O.scale_of_int(O.scale_int(float(s)))) / float(s)
+        assert 2 ** -0.0501 <= r <= 2 ** 0.0501
+
+
+def test_meta_int_worked_examples():
+    """Hand-computed groups.  [-1.8, 1.9] at 2 bits: scale 3.7/3 = 1.2333, log2 = 0.3025 -> scale_int 3, decoded
+    2^0.3 = 1.2311; zero = round(1.8/1.2311 = 1.46) = 1.  [0.5, 2] at 2 bits: the range is widened to [0, 2]:
+    2/3 -> log2 = -0.585 -> -6, zero 0.  [-4, -1] at 4 bits: widened to [-4, 0]: 4/15 -> log2 = -1.907 -> -19,
+    decoded 2^-1.9 = 0.26794, zero = round(4/0.26794 = 14.93) = 15.  A group of zeros: lowest scale, zero 0."""
+    k, z, sd, zf = O.meta_int(-1.8, 1.9, 2)
+    assert (k, z) == (3, 1) and abs(float(sd) - 2 ** 0.3) < 1e-6 and abs(float(zf) + 2 ** 0.3) < 1e-6
+    k, z, sd, zf = O.meta_int(0.5, 2.0, 2)
+    assert (k, z) == (-6, 0) and float(zf) == 0.0
+    k, z, sd, zf = O.meta_int(-4.0, -1.0, 4)
+    assert (k, z) == (-19, 15) and abs(float(zf) + 15 * 2 ** -1.9) < 1e-5
+    k, z, sd, zf = O.meta_int(0.0, 0.0, 3)
+    assert (k, z) == (-128, 0) and float(zf) == 0.0
+    # the zero always fits its byte: it is at most about qmax * 2^(1/20) + 1/2
+    rng = np.random.default_rng(9)
+    for _ in range(2000):
+        lo, hi = np.sort(rng.standard_normal(2) * 10.0 ** rng.uniform(-3, 3))
+        bits = int(rng.integers(2, 9))
+        k, z, sd, zf = O.meta_int(float(np.float32(lo)), float(np.float32(hi)), bits)
+        qmax = 2 ** bits - 1
+        assert 0 <= z <= min(255, int(qmax * 2 ** 0.05 + 1))
+        assert float(zf) == -float(np.float32(z) * sd)
+        if z < 255 and -128 < k < 127:
+            assert abs(float(zf) - min(float(np.float32(lo)), 0.0)) <= float(sd) * 0.5001
+
+
+@pytest.mark.parametrize("bits", range(2, 9))
+@pytest.mark.parametrize("flags", [INT, SR | INT])
+def test_integer_metadata_is_textbook_zero_point_quantization(bits, flags):
+    """With integer metadata the codes are the usual affine quantization with an integer zero-point,
+    q = clamp(round(x / s) + z, 0, qmax), recomputed here in float64 from the stored bytes; decoding is
+    (q - z) * s.  Codes may differ only where x / s is within 1e-4 of a tie."""
+    rng = np.random.default_rng(bits * 5 + flags)
+    qmax = 2 ** bits - 1
+    for kind in ("normal", "outlier", "coarse", "positive", "const"):
+        for G in (32, 128):
+            x = rand_group(rng, G, kind)
+            codes, s, zf, sv, si = O.quantize_group(x, bits, flags)
+            xf = f32(x).astype(np.float64)
+            rest = np.ones(G, bool)
+            if flags & SR:
+                rest[[int(si[0]), int(si[1])]] = False
+                assert codes[int(si[0])] == 0 and codes[int(si[1])] == 0
+            lo, hi = xf[rest].min(), xf[rest].max()
+            k, z, sd, zf2 = O.meta_int(lo, hi, bits)
+            assert (s, zf) == (sd, zf2)
+            # Eq. 1 on the widened range, in float64
+            s64 = (max(hi, 0.0) - min(lo, 0.0)) / qmax
+            if s64 > 0:
+                t = np.log2(s64) * 10
+                if abs(t - np.floor(t) - 0.5) > 1e-4:
+                    assert k == int(np.clip(np.rint(t), -128, 127))
+            t = xf / float(sd)
+            want = np.clip(np.rint(t) + z, 0, qmax)
+            near_tie = np.abs(t - np.floor(t) - 0.5) < 1e-4
+            ok = (codes == want) | near_tie | ~rest
+            assert ok.all()
+            assert codes.max() <= qmax
+            # error: half a step inside the covered range; the top may clamp by the 2^(1/20) slack of Eq. 1
+            v = (codes.astype(np.float64) - z) * float(sd)
+            err = np.abs(v - xf)[rest]
+            assert np.all(err <= float(sd) * (1.0 + 0.036 * qmax))
+            inside = ((t + z) <= qmax + 0.5)[rest]
+            assert np.all(err[inside] <= float(sd) * (0.5 + 1e-3))
+
+
+@pytest.mark.parametrize("bits,group", [(2, 32), (3, 32), (4, 32), (2, 128), (5, 64), (8, 256)])
+def test_roundtrip_record_with_integer_metadata(bits, group):
+    n = 4096
+    x = W.tensor(1, 0, rows=1, cols=n).reshape(-1)
+    xf = f32(x)
+    flags = SR | INT
+    packed = O.quantize_pack(x, bits, group, flags)
+    L = O.get_layout(n, bits, group, flags)
+    v = O.unpack_dequant(packed, n, bits, group, flags, O.DT_FP32)
+    vb = O.unpack_dequant(packed, n, bits, group, flags, O.DT_BF16)
+    kb = packed[L.off_scale:L.off_scale + L.n_groups].view(np.int8)
+    zb = packed[L.off_zero:L.off_zero + L.n_groups]
+    idx = packed[L.off_spike_idx:L.off_spike_idx + 2 * L.n_groups].reshape(-1, 2).astype(np.int64)
+    pos = (np.arange(L.n_groups)[:, None] * group + idx).reshape(-1)
+    spike = np.zeros(n, bool)
+    spike[pos] = True
+    assert np.array_equal(vb[spike], x[spike]) and np.array_equal(v[spike], xf[spike])  # Section 3.3: restored exactly
+    codes = O.unpack_codes(packed, n, bits, group, flags)
+    sd = np.exp2(kb.astype(np.float64) / 10)
+    want = (codes.astype(np.float64) - np.repeat(zb, group)) * np.repeat(sd, group)  # (q - z) * 2^(k/10)
+    # two fp32 roundings: the offset z * s, then the fused multiply-add
+    tol = 2.0 ** -22 * (codes + np.repeat(zb, group).astype(np.float64)) * np.repeat(sd, group) + 1e-30
+    assert np.all(np.abs(v - want)[~spike] <= tol[~spike])
+    assert np.array_equal(vb[~spike], W.f32_to_bf16_bits(v[~spike]))
+    for g in (0, 5, L.n_groups - 1):
+        cg, s, zf, sv, si = O.quantize_group(x[g * group:(g + 1) * group], bits, flags)
+        assert np.array_equal(codes[g * group:(g + 1) * group], cg)
+        assert float(s) == float(O.scale_of_int(int(kb[g]))) and float(zf) == -float(np.float32(zb[g]) * s)
+    # at the low widths Eq. 1 is meant for, the bytes cost little accuracy against bf16 metadata (within 1 dB on
+    # this data); at 7 and 8 bits the 2^(1/20) slack of the scale clamps the top codes and costs several dB
+    if bits <= 5:
+        v16 = O.unpack_dequant(O.quantize_pack(x, bits, group, SR), n, bits, group, SR)
+        e_int, e_16 = np.mean((v - xf) ** 2), np.mean((v16 - xf) ** 2)
+        assert e_int <= e_16 * 10 ** 0.1
+
+
+def test_reduce_requant_with_integer_metadata():
+    n, N = 4096, 4
+    fmt = (2, 32, SR | INT)
+    xs = [W.tensor(2, p, rows=1, cols=n).reshape(-1) for p in range(N)]
+    peers = [O.quantize_pack(x, *fmt) for x in xs]
+    out, s = O.reduce_requant(peers, n, fmt, want_sum=True)
+    vs = [O.unpack_dequant(p, n, *fmt).astype(np.float64) for p in peers]
+    exact = np.sum(vs, axis=0)
+    assert np.all(np.abs(s - exact) <= N * 2.0 ** -23 * np.sum(np.abs(vs), axis=0) + 1e-30)
+    assert np.array_equal(out, O.quantize_pack(W.f32_to_bf16_bits(s), *fmt))
+    out2 = O.reduce_requant(peers, n, fmt, (4, 32, SR))  # integer metadata in, bf16 metadata out
+    assert np.array_equal(out2, O.quantize_pack(W.f32_to_bf16_bits(s), 4, 32, SR))
 
 
 # ---- dispatch (Sections 3.1, 4.4) ----------------------------------------------------------------------------
