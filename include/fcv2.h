@@ -29,6 +29,12 @@
  *   scale and zero are bf16 (fp32 with FCV2_F_META_FP32); zero is the float offset (the group's new minimum),
  *   spike_val[2g], spike_val[2g+1] are the raw bf16 bits of the group's min and max element, spike_idx the
  *   matching in-group positions as bytes.  The code stored at a spike position is 0.
+ *   With FCV2_F_META_INT (Section 3.3, Eq. 1 and the second row of Table 4) scale and zero take one byte each:
+ *   scale[g] is the signed byte scale_int = round(log2(scale) * 10), clamped to [-128, 127], and stands for the
+ *   scale 2^(scale_int / 10) rounded to fp32; zero[g] is the unsigned zero-point round(-lo / scale) of the range
+ *   widened to contain 0 and stands for the offset -(zero * scale); element = fma(code, scale, offset).  Meant for
+ *   the low widths (at 7 and 8 bits the 2^(1/20) granularity of the scale costs several dB).  FCV2_F_META_FP32 and
+ *   FCV2_F_META_INT exclude each other.
  */
 #ifndef FCV2_H
 #define FCV2_H
@@ -49,7 +55,7 @@ enum {
     FCV2_ERR_LAUNCH = -5       /* the HIP runtime refused the launch */
 };
 
-enum { FCV2_F_SPIKE = 1u, FCV2_F_META_FP32 = 2u };
+enum { FCV2_F_SPIKE = 1u, FCV2_F_META_FP32 = 2u, FCV2_F_META_INT = 4u };
 enum { FCV2_DT_BF16 = 0, FCV2_DT_FP32 = 1 };
 
 #define FCV2_ABSENT UINT64_MAX
@@ -105,7 +111,7 @@ int fcv2_unpack_dequant_slices(const void* const* records_dev, uint32_t n_slices
  * round the sum to bf16 and quantize it again with fmt_out into packed_out_dev.
  * peers_dev is a HOST array of n_peers DEVICE pointers (copied at call time), 1 <= n_peers <= FCV2_MAX_PEERS.
  * sum_out_dev, if not NULL, receives the n fp32 sums (before the bf16 rounding).
- * fmt_in and fmt_out must agree in group and FCV2_F_SPIKE (bits and FCV2_F_META_FP32 may differ; equal bits take
+ * fmt_in and fmt_out must agree in group and FCV2_F_SPIKE (bits and the metadata flags may differ; equal bits take
  * the fast kernel); other pairs give FCV2_ERR_UNSUPPORTED. */
 int fcv2_reduce_requant(const void* const* peers_dev, int n_peers, uint64_t n, const fcv2_fmt_t* fmt_in,
                         const fcv2_fmt_t* fmt_out, void* packed_out_dev, float* sum_out_dev, void* hip_stream);

@@ -12,10 +12,15 @@
 //   scale = (hi - lo) / qmax in fp32 (IEEE division), stored rounded up to bf16 unless FCV2_F_META_FP32;
 //   inv = 1 / scale (IEEE division); code = clamp(rint((x - lo) * inv), 0, qmax), sub then mul, no FMA;
 //   decode = fma(code, scale, lo); reduction = fp32 adds in peer order; bf16 rounding = nearest even.
+//   With FCV2_F_META_INT (Section 3.3, Eq. 1) scale and zero are one byte each: the range is widened to contain 0,
+//   scale_int = round(log2(scale) * 10), the decoded scale is 2^(scale_int / 10), zero = round(-lo / scale) as an
+//   unsigned byte, the offset used by both sides is -(zero * scale), codes are clamped to [0, qmax].
 // Compile with -ffp-contract=off.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stdlib.h>
+
+#include <type_traits>
 
 #include "../../include/fcv2.h"
 #include "fcv2_bits.h"
@@ -31,10 +36,14 @@ struct PeerPtrs {
 };
 
 struct GroupMeta {
-    float s, lo;
+    float s, lo;  // scale and offset as the receiver reconstructs them
     uint32_t sv;  // raw bf16 bits: min spike | max spike << 16
     uint32_t si;  // in-group positions: min | max << 8
+    uint32_t raw_s, raw_z;  // integer metadata only: the scale_int byte and the zero byte
 };
+
+// How scale and zero are stored.
+constexpr uint32_t kMetaBf16 = 0, kMetaFp32 = 1, kMetaInt = 2;
 
 // ---- cross-lane helpers -------------------------------------------------------------------------------------
 template <int CTRL> __device__ __forceinline__ uint32_t dpp(uint32_t v) {
@@ -119,7 +128,7 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // the two smallest composites (key << 16 | position) and the two smallest of (~key << 16 | position) are
 // tracked in one pass; the smallest of each gives a spike and its position, the second the new range.
 template <int BITS, int EPL, int LPG, bool SR>
-__device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint32_t lig, bool meta_fp32, uint32_t (&c)[EPL / 4],
+__device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint32_t lig, uint32_t mode, uint32_t (&c)[EPL / 4],
                                               GroupMeta& m) {
     const uint32_t lbase = lig * (uint32_t)EPL;
     uint32_t a1, a2, b1, b2;  // two smallest composites (a: minimum side, b: maximum side)
@@ -148,13 +157,13 @@ __device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint
     }
     a1 += lbase;
     b1 += lbase;
-    uint32_t klo, khi, imax = 0xFFFFu;
+    uint32_t klo, khi, imin = 0xFFFFu, imax = 0xFFFFu;
     if (SR) {
         a2 += lbase;
         b2 += lbase;
         group_min2<LPG>(a1, a2);
         group_min2<LPG>(b1, b2);
-        const uint32_t imin = a1 & 0xFFFFu;
+        imin = a1 & 0xFFFFu;
         // a constant group: the first maximum is the minimum itself, take the next position
         imax = ((b1 & 0xFFFFu) == imin) ? (b2 & 0xFFFFu) : (b1 & 0xFFFFu);
         klo = a2 >> 16;
@@ -171,31 +180,69 @@ __device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint
     }
     const float lo = u2f(bf16_of_key(klo) << 16);
     const float hi = u2f(bf16_of_key(khi) << 16);
-    const float s32 = div_by_qmax<(1 << BITS) - 1>(__fsub_rn(hi, lo));
-    float s = 1.0f;
-    if (s32 >= 0x1p-64f) s = meta_fp32 ? s32 : u2f(bf16_round_up_bits(f2u(s32)));
-    float inv;
-    if (!(s <= 0x1p+120f))
-        inv = __fdiv_rn(1.0f, s);  // reciprocal near the denormal range, or an infinite scale
-    else
+    constexpr int QMAX = (1 << BITS) - 1;
+    float s, off, inv;
+    uint32_t raw_s = 0, raw_z = 0;
+    if (mode == kMetaInt) {
+        // Eq. 1: byte-sized scale and zero-point over the range widened to contain 0
+        const float lo0 = (lo < 0.0f) ? lo : 0.0f, hi0 = (hi > 0.0f) ? hi : 0.0f;
+        const ScaleInt si = scale_int_of(div_by_qmax<QMAX>(__fsub_rn(hi0, lo0)));
+        s = si.s;  // in [2^-12.8, 2^12.7]
         inv = rcp_newton(s);
+        raw_z = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn(-lo0, inv), 0, 0u);  // nearest even, saturated to [0, 255]
+        raw_s = (uint32_t)si.k & 0xFFu;
+        off = -__fmul_rn((float)raw_z, s);
+    } else {
+        const float s32 = div_by_qmax<QMAX>(__fsub_rn(hi, lo));
+        s = 1.0f;
+        if (s32 >= 0x1p-64f) s = (mode == kMetaFp32) ? s32 : u2f(bf16_round_up_bits(f2u(s32)));
+        if (!(s <= 0x1p+120f))
+            inv = __fdiv_rn(1.0f, s);  // reciprocal near the denormal range, or an infinite scale
+        else
+            inv = rcp_newton(s);
+        off = lo;
+    }
     m.s = s;
-    m.lo = lo;
+    m.lo = off;
+    m.raw_s = raw_s;
+    m.raw_z = raw_z;
 
-    // code = rint((x - lo) * inv) clamped to [0, qmax].  v_cvt_pk_u8_f32 rounds to nearest even and saturates
-    // to [0, 255] (NaN -> 0), and for every position outside the spikes (x - lo) * inv <= qmax * (1 + 2^-22),
-    // so the conversion alone already is the clamped code; the minimum spike lands on 0 by itself, the
-    // maximum spike's byte is cleared below.
+    // code = rint((x - off) * inv) clamped to [0, qmax].  v_cvt_pk_u8_f32 rounds to nearest even and saturates
+    // to [0, 255] (NaN -> 0).  With float metadata (x - lo) * inv <= qmax * (1 + 2^-22) for every position outside
+    // the spikes, so the conversion alone already is the clamped code; the minimum spike lands on 0 by itself, the
+    // maximum spike's byte is cleared below.  With integer metadata the decoded scale may be up to 2^(1/20) below
+    // the exact one, so the top is clamped explicitly, and the minimum spike's byte is cleared as well.
+    if (BITS < 8 && mode == kMetaInt) {
 #pragma unroll
-    for (int i = 0; i < EPL / 4; ++i) {
-        uint32_t cc = 0;
+        for (int i = 0; i < EPL / 4; ++i) {
+            uint32_t cc = 0;
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int j = 4 * i + b;
-            const float x = u2f((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
-            cc = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn(__fsub_rn(x, lo), inv), b, cc);
+            for (int b = 0; b < 4; ++b) {
+                const int j = 4 * i + b;
+                const float x = u2f((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
+                cc = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fminf(__fmul_rn(__fsub_rn(x, off), inv), (float)QMAX), b, cc);
+            }
+            c[i] = cc;
         }
-        c[i] = cc;
+    } else {
+#pragma unroll
+        for (int i = 0; i < EPL / 4; ++i) {
+            uint32_t cc = 0;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int j = 4 * i + b;
+                const float x = u2f((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
+                cc = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn(__fsub_rn(x, off), inv), b, cc);
+            }
+            c[i] = cc;
+        }
+    }
+    if (SR && mode == kMetaInt) {
+        const uint32_t rel = imin - lbase;  // position inside this lane, or >= EPL
+        const uint32_t clr = ~(0xFFu << ((rel & 3u) * 8u));
+        const uint32_t dw = rel >> 2;
+#pragma unroll
+        for (int i = 0; i < EPL / 4; ++i) c[i] &= (dw == (uint32_t)i) ? clr : 0xFFFFFFFFu;
     }
     if (SR) {
         const uint32_t rel = imax - lbase;  // position inside this lane, or >= EPL
@@ -250,8 +297,11 @@ template <int BITS, int EPL> __device__ __forceinline__ void store_planes(uint8_
     }
 }
 
-template <bool SR> __device__ __forceinline__ void store_meta(uint8_t* base, const Rec& r, uint32_t g, const GroupMeta& m, bool meta_fp32) {
-    if (meta_fp32) {
+template <bool SR> __device__ __forceinline__ void store_meta(uint8_t* base, const Rec& r, uint32_t g, const GroupMeta& m, uint32_t mode) {
+    if (mode == kMetaInt) {
+        base[r.scale + g] = (uint8_t)m.raw_s;
+        base[r.zero + g] = (uint8_t)m.raw_z;
+    } else if (mode == kMetaFp32) {
         *reinterpret_cast<float*>(base + (r.scale + 4u * g)) = m.s;
         *reinterpret_cast<float*>(base + (r.zero + 4u * g)) = m.lo;
     } else {
@@ -365,26 +415,32 @@ struct MetaOffsets {
     uint32_t to_f32;  // left shift that turns a stored scale/zero into fp32 bits: 16 for bf16, 0 for fp32
 };
 
-template <int LPG, bool SR> __device__ __forceinline__ MetaOffsets meta_offsets(const Rec& r, uint32_t L, bool meta_fp32) {
+template <int LPG, bool SR> __device__ __forceinline__ MetaOffsets meta_offsets(const Rec& r, uint32_t L, uint32_t mode) {
     const uint32_t g = L / LPG, item = L & 3u;
-    const uint32_t msz = meta_fp32 ? 4u : 2u;
+    const uint32_t msz = (mode == kMetaFp32) ? 4u : (mode == kMetaInt) ? 1u : 2u;
     uint32_t at = r.scale + msz * g;               // item 0, and every item when there are no spikes
     if (item == 1u) at = r.zero + msz * g;
     if (SR && item == 2u) at = r.spike_val + 4u * g;
     if (SR && item == 3u) at = r.spike_idx + 2u * g;
     MetaOffsets o;
     o.at = at & ~3u;                                 // aligned dword that holds the item
-    o.shift = (at & 2u) * 8u;
-    o.to_f32 = meta_fp32 ? 0u : 16u;
+    o.shift = (at & 3u) * 8u;
+    o.to_f32 = (mode == kMetaFp32) ? 0u : 16u;
     return o;
 }
 
-template <bool SR> __device__ __forceinline__ GroupMeta spread_meta(uint32_t raw, const MetaOffsets& o) {
+template <bool SR, bool INT_META> __device__ __forceinline__ GroupMeta spread_meta(uint32_t raw, const MetaOffsets& o) {
     const uint32_t val = raw >> o.shift;
     GroupMeta m;
     const uint32_t sb = quad_bcast<0>(val), zb = quad_bcast<1>(val);
-    m.s = u2f(sb << o.to_f32);
-    m.lo = u2f(zb << o.to_f32);
+    if (INT_META) {  // Eq. 1 inverted: 2^(scale_int / 10), offset = -(zero * scale)
+        m.s = scale_of_int((int)(int8_t)(sb & 0xFFu));
+        m.lo = -__fmul_rn((float)(zb & 0xFFu), m.s);
+    } else {
+        m.s = u2f(sb << o.to_f32);
+        m.lo = u2f(zb << o.to_f32);
+    }
+    m.raw_s = m.raw_z = 0;
     m.sv = SR ? quad_bcast<2>(val) : 0u;
     m.si = SR ? (quad_bcast<3>(val) & 0xFFFFu) : 0u;
     return m;
@@ -446,7 +502,7 @@ __device__ __forceinline__ void tile_transpose(const TileIn& t, uint4* wave_lds,
 // quantized, so memory and arithmetic overlap inside every wave.
 template <int BITS, int LPG, bool SR>
 __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restrict__ x, uint32_t n_lanes, uint8_t* __restrict__ out,
-                                                            Rec rec, uint32_t meta_fp32, uint32_t slice_lanes,
+                                                            Rec rec, uint32_t meta_mode, uint32_t slice_lanes,
                                                             uint64_t record_stride) {
     // The tensor may be cut into equal slices, each packed into a record of its own (records `record_stride` bytes
     // apart); slice_lanes is a multiple of 64 then, so a wave's tile lies in one slice.  One slice: slice_lanes = n_lanes.
@@ -468,11 +524,11 @@ __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restr
         if (L < n_lanes) {  // groups never straddle the end: whole groups are in or out together
             uint32_t c[EPL / 4];
             GroupMeta m;
-            quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_fp32 != 0, c, m);
+            quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode, c, m);
             uint8_t* o = out + slice * record_stride;
             const uint32_t Lr = L - slice * slice_lanes;  // lane inside the record
             store_planes<BITS, EPL>(o, rec, Lr, c);
-            if (lig == 0) store_meta<SR>(o, rec, Lr / LPG, m, meta_fp32 != 0);
+            if (lig == 0) store_meta<SR>(o, rec, Lr / LPG, m, meta_mode);
         }
     };
     // Two tiles are kept in flight per wave (two register sets, ping-pong, so loaded data is never moved); the
@@ -501,7 +557,7 @@ __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restr
 // positions (Section 3.3: restored in place) and (b) the global stores are fully coalesced 16-byte pieces.
 template <int BITS, int LPG, bool SR, bool OUT_FP32>
 __global__ __launch_bounds__(kBlock) void k_unpack_dequant_t(PeerPtrs records, uint32_t slice_lanes, Rec rec, uint32_t n_lanes,
-                                                             uint4* __restrict__ out, uint32_t meta_fp32) {
+                                                             uint4* __restrict__ out, uint32_t meta_mode) {
     constexpr int EPL = kEplStream;
     constexpr int ROW = OUT_FP32 ? 9 : kRowU4;  // uint4 per lane row incl. one of padding
     constexpr int NP = OUT_FP32 ? 8 : 4;       // 16-byte pieces per lane
@@ -519,7 +575,10 @@ __global__ __launch_bounds__(kBlock) void k_unpack_dequant_t(PeerPtrs records, u
         const uint32_t g = Lr / LPG;
         const RawPlanes<EPL> r = load_planes<BITS, EPL>(in, rec, Lr);
         float s, lo;
-        if (meta_fp32) {
+        if (meta_mode == kMetaInt) {
+            s = scale_of_int((int)(int8_t)in[rec.scale + g]);
+            lo = -__fmul_rn((float)in[rec.zero + g], s);
+        } else if (meta_mode == kMetaFp32) {
             s = *reinterpret_cast<const float*>(in + (rec.scale + 4u * g));
             lo = *reinterpret_cast<const float*>(in + (rec.zero + 4u * g));
         } else {
@@ -627,44 +686,52 @@ template <int EPL> __device__ __forceinline__ void patch_spikes(const GroupMeta&
 template <int BITS, int EPL, int LPG, bool SR>
 __global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
                                                            uint8_t* __restrict__ out, Rec rec_out, float* __restrict__ sum_out,
-                                                           uint32_t meta_fp32_in, uint32_t meta_fp32_out) {
+                                                           uint32_t meta_mode_in, uint32_t meta_mode_out) {
     constexpr int ROW = EPL / 4 + 1;  // uint4 per private patch row, one of padding: conflict-free 16-byte accesses
     __shared__ uint4 lds[kBlock * ROW];
     const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
     if (L >= n_lanes) return;
     const uint32_t lig = threadIdx.x & (LPG - 1);
     uint4* row = &lds[threadIdx.x * ROW];
-    const MetaOffsets mo = meta_offsets<LPG, SR>(rec_in, L, meta_fp32_in != 0);
+    const MetaOffsets mo = meta_offsets<LPG, SR>(rec_in, L, meta_mode_in);
     // -0 is the identity of fp32 addition for every value including -0, so the chain below starts exactly at v_0
     float acc[EPL];
 #pragma unroll
     for (int j = 0; j < EPL; ++j) acc[j] = -0.0f;
-    auto add_peer = [&](const RawPlanes<EPL>& r, uint32_t mraw) {
-        const GroupMeta m = spread_meta<SR>(mraw, mo);
-        float v[EPL];
-        dequant_mix<BITS, EPL>(r, m.s, m.lo, v);
-        if (SR) patch_spikes<EPL>(m, lig, row, v);
+    // The peer loop exists twice, once per kind of metadata decoding, chosen by one uniform branch outside it.
+    auto sum_peers = [&](auto int_meta) {
+        constexpr bool INT_META = decltype(int_meta)::value;
+        auto add_peer = [&](const RawPlanes<EPL>& r, uint32_t mraw) {
+            const GroupMeta m = spread_meta<SR, INT_META>(mraw, mo);
+            float v[EPL];
+            dequant_mix<BITS, EPL>(r, m.s, m.lo, v);
+            if (SR) patch_spikes<EPL>(m, lig, row, v);
 #pragma unroll
-        for (int j = 0; j < EPL; ++j) acc[j] = __fadd_rn(acc[j], v[j]);
-    };
-    int p = 0;
-    // four peers at a time: all loads first, so their latencies overlap
-    for (; p + 4 <= n_peers; p += 4) {
-        RawPlanes<EPL> r[4];
-        uint32_t mraw[4];
+            for (int j = 0; j < EPL; ++j) acc[j] = __fadd_rn(acc[j], v[j]);
+        };
+        int p = 0;
+        // four peers at a time: all loads first, so their latencies overlap
+        for (; p + 4 <= n_peers; p += 4) {
+            RawPlanes<EPL> r[4];
+            uint32_t mraw[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            r[i] = load_planes<BITS, EPL>(peers.base[p + i], rec_in, L);
-            mraw[i] = *reinterpret_cast<const uint32_t*>(at32(peers.base[p + i], mo.at));
+            for (int i = 0; i < 4; ++i) {
+                r[i] = load_planes<BITS, EPL>(peers.base[p + i], rec_in, L);
+                mraw[i] = *reinterpret_cast<const uint32_t*>(at32(peers.base[p + i], mo.at));
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) add_peer(r[i], mraw[i]);
         }
-#pragma unroll
-        for (int i = 0; i < 4; ++i) add_peer(r[i], mraw[i]);
-    }
-    for (; p < n_peers; ++p) {
-        const RawPlanes<EPL> r = load_planes<BITS, EPL>(peers.base[p], rec_in, L);
-        const uint32_t mraw = *reinterpret_cast<const uint32_t*>(at32(peers.base[p], mo.at));
-        add_peer(r, mraw);
-    }
+        for (; p < n_peers; ++p) {
+            const RawPlanes<EPL> r = load_planes<BITS, EPL>(peers.base[p], rec_in, L);
+            const uint32_t mraw = *reinterpret_cast<const uint32_t*>(at32(peers.base[p], mo.at));
+            add_peer(r, mraw);
+        }
+    };
+    if (meta_mode_in == kMetaInt)
+        sum_peers(std::true_type{});
+    else
+        sum_peers(std::false_type{});
     if (sum_out) {
         float4* dst = reinterpret_cast<float4*>(sum_out) + (EPL / 4) * (uint64_t)L;
 #pragma unroll
@@ -675,9 +742,9 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n
     for (int d = 0; d < EPL / 2; ++d) w[d] = pack_bf16(acc[2 * d], acc[2 * d + 1]);
     uint32_t c[EPL / 4];
     GroupMeta m;
-    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_fp32_out != 0, c, m);
+    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode_out, c, m);
     store_planes<BITS, EPL>(out, rec_out, L, c);
-    if (lig == 0) store_meta<SR>(out, rec_out, L / LPG, m, meta_fp32_out != 0);
+    if (lig == 0) store_meta<SR>(out, rec_out, L / LPG, m, meta_mode_out);
 }
 
 // The same step when the peers' bit width differs from the output's: the input width is a run-time value
@@ -686,21 +753,22 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n
 template <int BITS_OUT, int EPL, int LPG, bool SR>
 __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers, int n_peers, uint32_t bits_in, uint32_t n_lanes,
                                                                  Rec rec_in, uint8_t* __restrict__ out, Rec rec_out,
-                                                                 float* __restrict__ sum_out, uint32_t meta_fp32_in,
-                                                                 uint32_t meta_fp32_out) {
+                                                                 float* __restrict__ sum_out, uint32_t meta_mode_in,
+                                                                 uint32_t meta_mode_out) {
     constexpr int ROW = EPL / 4 + 1;
     __shared__ uint4 lds[kBlock * ROW];
     const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
     if (L >= n_lanes) return;
     const uint32_t lig = threadIdx.x & (LPG - 1);
     uint4* row = &lds[threadIdx.x * ROW];
-    const MetaOffsets mo = meta_offsets<LPG, SR>(rec_in, L, meta_fp32_in != 0);
+    const MetaOffsets mo = meta_offsets<LPG, SR>(rec_in, L, meta_mode_in);
     float acc[EPL];
 #pragma unroll
     for (int j = 0; j < EPL; ++j) acc[j] = -0.0f;
     for (int p = 0; p < n_peers; ++p) {
         const uint8_t* base = peers.base[p];
-        const GroupMeta m = spread_meta<SR>(*reinterpret_cast<const uint32_t*>(at32(base, mo.at)), mo);
+        const uint32_t mraw = *reinterpret_cast<const uint32_t*>(at32(base, mo.at));
+        const GroupMeta m = (meta_mode_in == kMetaInt) ? spread_meta<SR, true>(mraw, mo) : spread_meta<SR, false>(mraw, mo);
         float v[EPL];
         switch (bits_in) {
 #define FCV2_CASE(B)                                                      \
@@ -733,9 +801,9 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
     for (int d = 0; d < EPL / 2; ++d) w[d] = pack_bf16(acc[2 * d], acc[2 * d + 1]);
     uint32_t c[EPL / 4];
     GroupMeta m;
-    quantize_lane<BITS_OUT, EPL, LPG, SR>(w, lig, meta_fp32_out != 0, c, m);
+    quantize_lane<BITS_OUT, EPL, LPG, SR>(w, lig, meta_mode_out, c, m);
     store_planes<BITS_OUT, EPL>(out, rec_out, L, c);
-    if (lig == 0) store_meta<SR>(out, rec_out, L / LPG, m, meta_fp32_out != 0);
+    if (lig == 0) store_meta<SR>(out, rec_out, L / LPG, m, meta_mode_out);
 }
 
 // ---- dispatch: stable counting sort of the routed copies by expert, then quantize-and-scatter ------------------------
@@ -861,7 +929,7 @@ __global__ __launch_bounds__(kChunk) void k_dispatch_rank(const int32_t* __restr
 template <int BITS, int LPG, bool SR>
 __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __restrict__ x, uint32_t n_lanes, uint32_t lanes_per_row,
                                                              uint32_t K, const int32_t* __restrict__ dest, uint8_t* __restrict__ send,
-                                                             Rec rec, uint32_t row_bytes, uint32_t meta_fp32) {
+                                                             Rec rec, uint32_t row_bytes, uint32_t meta_mode) {
     constexpr int EPL = kEplStream;
     __shared__ uint4 lds[kWaves][64 * kRowU4];
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -877,7 +945,7 @@ __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __rest
     const uint32_t r = L - t * lanes_per_row;  // lane inside the row
     uint32_t c[EPL / 4];
     GroupMeta m;
-    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_fp32 != 0, c, m);
+    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode, c, m);
     const uint32_t g = r / LPG;
     // The send buffer is addressed with 32-bit offsets (checked on the host): a row's offset is one 24-bit multiply,
     // every store one add on top of per-lane offsets computed once.
@@ -891,7 +959,7 @@ __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __rest
         if (P::w1) q1 |= (pack_plane1<P::sh1, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFu) << (8 * u);
     }
     const uint32_t o8 = rec.plane8 + 32u * r, o4 = rec.plane4 + 16u * r, o2 = rec.plane2 + 8u * r, o1 = rec.plane1 + 4u * r;
-    const uint32_t msz = meta_fp32 ? 4u : 2u;
+    const uint32_t msz = (meta_mode == kMetaFp32) ? 4u : (meta_mode == kMetaInt) ? 1u : 2u;
     const uint32_t os = rec.scale + msz * g, oz = rec.zero + msz * g, ov = rec.spike_val + 4u * g, oi = rec.spike_idx + 2u * g;
     for (uint32_t k0 = 0; k0 < K; k0 += 8) {
         int32_t rows[8];  // all destinations first: the loads overlap instead of queueing one behind the other
@@ -909,7 +977,10 @@ __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __rest
             if (P::w2) *reinterpret_cast<uint2*>(send + (ro + o2)) = make_uint2(q2[0] | (q2[1] << 16), q2[2] | (q2[3] << 16));
             if (P::w1) *reinterpret_cast<uint32_t*>(send + (ro + o1)) = q1;
             if (lig == 0) {
-                if (meta_fp32) {
+                if (meta_mode == kMetaInt) {
+                    send[ro + os] = (uint8_t)m.raw_s;
+                    send[ro + oz] = (uint8_t)m.raw_z;
+                } else if (meta_mode == kMetaFp32) {
                     *reinterpret_cast<float*>(send + (ro + os)) = m.s;
                     *reinterpret_cast<float*>(send + (ro + oz)) = m.lo;
                 } else {
@@ -935,7 +1006,12 @@ __global__ __launch_bounds__(kBlock) void k_stream_copy(const uint4* __restrict_
 static bool fmt_supported(const fcv2_fmt_t* f) {
     if (f->bits < 2 || f->bits > 8) return false;
     if (f->group != 32 && f->group != 64 && f->group != 128 && f->group != 256) return false;
-    return (f->flags & ~(FCV2_F_SPIKE | FCV2_F_META_FP32)) == 0;
+    if ((f->flags & ~(FCV2_F_SPIKE | FCV2_F_META_FP32 | FCV2_F_META_INT)) != 0) return false;
+    return (f->flags & (FCV2_F_META_FP32 | FCV2_F_META_INT)) != (FCV2_F_META_FP32 | FCV2_F_META_INT);  // one or the other
+}
+
+static inline uint32_t meta_mode_of(const fcv2_fmt_t* f) {
+    return (f->flags & FCV2_F_META_INT) ? kMetaInt : (f->flags & FCV2_F_META_FP32) ? kMetaFp32 : kMetaBf16;
 }
 
 static inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
@@ -1004,27 +1080,27 @@ static unsigned persistent_grid(uint32_t n_tiles) {
 }
 
 template <int BITS, int G, bool SR> struct LaunchQuantize {
-    static int run(const void* x, uint64_t n, void* out, const Rec& rec, uint32_t meta_fp32, uint32_t n_slices,
+    static int run(const void* x, uint64_t n, void* out, const Rec& rec, uint32_t meta_mode, uint32_t n_slices,
                    uint64_t record_stride, hipStream_t st) {
         constexpr int EPL = kEplStream;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
         const uint32_t n_tiles = (n_lanes + 63) / 64;
         hipLaunchKernelGGL((k_quantize_pack_t<BITS, G / EPL, SR>), dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
-                           (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_fp32, n_lanes / n_slices, record_stride);
+                           (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_mode, n_lanes / n_slices, record_stride);
         return launch_status();
     }
 };
 template <int BITS, int G, bool SR> struct LaunchUnpack {
     static int run(const PeerPtrs& records, uint32_t n_slices, const Rec& rec, uint64_t n, void* out, uint32_t out_fp32,
-                   uint32_t meta_fp32, hipStream_t st) {
+                   uint32_t meta_mode, hipStream_t st) {
         constexpr int EPL = kEplStream;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
         if (out_fp32)
             hipLaunchKernelGGL((k_unpack_dequant_t<BITS, G / EPL, SR, true>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
-                               records, n_lanes / n_slices, rec, n_lanes, (uint4*)out, meta_fp32);
+                               records, n_lanes / n_slices, rec, n_lanes, (uint4*)out, meta_mode);
         else
             hipLaunchKernelGGL((k_unpack_dequant_t<BITS, G / EPL, SR, false>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
-                               records, n_lanes / n_slices, rec, n_lanes, (uint4*)out, meta_fp32);
+                               records, n_lanes / n_slices, rec, n_lanes, (uint4*)out, meta_mode);
         return launch_status();
     }
 };
@@ -1050,11 +1126,11 @@ template <int BITS, int G, bool SR> struct LaunchReduceMixed {  // BITS = output
 };
 template <int BITS, int G, bool SR> struct LaunchDispatch {
     static int run(const void* x, uint64_t n, uint32_t H, uint32_t K, const int32_t* dest, uint8_t* send, const Rec& rec,
-                   uint32_t row_bytes, uint32_t meta_fp32, hipStream_t st) {
+                   uint32_t row_bytes, uint32_t meta_mode, hipStream_t st) {
         constexpr int EPL = kEplStream;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
         hipLaunchKernelGGL((k_dispatch_quant_t<BITS, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
-                           (const uint4*)x, n_lanes, H / EPL, K, dest, send, rec, row_bytes, meta_fp32);
+                           (const uint4*)x, n_lanes, H / EPL, K, dest, send, rec, row_bytes, meta_mode);
         return launch_status();
     }
 };
@@ -1100,7 +1176,7 @@ int fcv2_get_layout(uint64_t n, const fcv2_fmt_t* fmt, uint32_t align, fcv2_layo
     if (n == 0 || n % fmt->group != 0 || n % 8 != 0) return FCV2_ERR_INVALID_ARG;
     if (align == 0 || (align & (align - 1)) != 0) return FCV2_ERR_INVALID_ARG;
     const uint64_t ng = n / fmt->group;
-    const uint64_t meta = (fmt->flags & FCV2_F_META_FP32) ? 4 : 2;
+    const uint64_t meta = (fmt->flags & FCV2_F_META_FP32) ? 4 : (fmt->flags & FCV2_F_META_INT) ? 1 : 2;
     const bool has8 = fmt->bits == 8, has4 = fmt->bits >= 4 && fmt->bits <= 7;
     const bool has2 = fmt->bits == 2 || fmt->bits == 3 || fmt->bits == 6 || fmt->bits == 7;
     const bool has1 = fmt->bits == 3 || fmt->bits == 5 || fmt->bits == 7;
@@ -1148,7 +1224,7 @@ int fcv2_quantize_pack_slices(const void* x, uint64_t n, uint32_t n_slices, cons
     if (rc != FCV2_OK) return rc;
     if (n_slices > 1 && (record_stride < l.total_bytes || record_stride % FCV2_TENSOR_ALIGN != 0)) return FCV2_ERR_INVALID_ARG;
     if (!aligned16(x) || !aligned16(packed)) return FCV2_ERR_ALIGN;
-    return by_format<LaunchQuantize>(fmt, x, n, packed, rec_of(l), (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0), n_slices,
+    return by_format<LaunchQuantize>(fmt, x, n, packed, rec_of(l), meta_mode_of(fmt), n_slices,
                                      record_stride, (hipStream_t)stream);
 }
 
@@ -1172,7 +1248,7 @@ int fcv2_unpack_dequant_slices(const void* const* records, uint32_t n_slices, ui
         pp.base[p] = (const uint8_t*)ptr;
     }
     return by_format<LaunchUnpack>(fmt, pp, n_slices, rec_of(l), n, out, (uint32_t)(out_dtype == FCV2_DT_FP32),
-                                   (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0), (hipStream_t)stream);
+                                   meta_mode_of(fmt), (hipStream_t)stream);
 }
 
 int fcv2_unpack_dequant(const void* packed, uint64_t n, const fcv2_fmt_t* fmt, void* out, int out_dtype, void* stream) {
@@ -1201,8 +1277,8 @@ int fcv2_reduce_requant(const void* const* peers, int n_peers, uint64_t n, const
         if (!aligned16(ptr)) return FCV2_ERR_ALIGN;
         pp.base[p] = (const uint8_t*)ptr;
     }
-    const uint32_t mf_in = (uint32_t)((fmt_in->flags & FCV2_F_META_FP32) != 0);
-    const uint32_t mf_out = (uint32_t)((fmt_out->flags & FCV2_F_META_FP32) != 0);
+    const uint32_t mf_in = meta_mode_of(fmt_in);
+    const uint32_t mf_out = meta_mode_of(fmt_out);
     if (fmt_in->bits != fmt_out->bits)
         return by_format<LaunchReduceMixed>(fmt_out, pp, n_peers, fmt_in->bits, n, rec_of(lin), packed_out, rec_of(lout), sum_out,
                                             mf_in, mf_out, (hipStream_t)stream);
@@ -1246,7 +1322,7 @@ int fcv2_dispatch_quant(const void* x, const int32_t* ids, uint32_t T, uint32_t 
                        (const int32_t*)totals, expert_offsets, dest, row_src);
     if (launch_status() != FCV2_OK) return FCV2_ERR_LAUNCH;
     return by_format<LaunchDispatch>(fmt, x, (uint64_t)T * H, H, K, (const int32_t*)dest, (uint8_t*)send,
-                                     rec_of(l), (uint32_t)l.total_bytes, (uint32_t)((fmt->flags & FCV2_F_META_FP32) != 0), st);
+                                     rec_of(l), (uint32_t)l.total_bytes, meta_mode_of(fmt), st);
 }
 
 int fcv2_stream_copy(const void* src, void* dst, uint64_t bytes, void* stream) {

@@ -12,7 +12,7 @@ from paper_2508_03760_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
 
-SR, F32 = fcv2.F_SPIKE, fcv2.F_META_FP32
+SR, F32, INT = fcv2.F_SPIKE, fcv2.F_META_FP32, fcv2.F_META_INT
 DEV = "cuda:0"
 
 
@@ -29,7 +29,7 @@ def to_dev_bf16(bits_u16):
 
 
 def sections(L, flags):
-    m = 4 if flags & F32 else 2
+    m = 4 if flags & F32 else 1 if flags & INT else 2
     out = []
     for w in (8, 4, 2, 1):
         off = getattr(L, f"off_plane{w}")
@@ -83,7 +83,7 @@ def check_codec(x_u16, bits, group, flags, what):
 def test_codec_all_formats(bits, group):
     n = 2048 * 3 + 3 * 256  # three full 256-lane blocks plus a partial one
     x = W.tensor(2, 0, rows=1, cols=n).reshape(-1)
-    for flags in (SR, 0, SR | F32, F32):
+    for flags in (SR, 0, SR | F32, F32, SR | INT, INT):
         check_codec(x, bits, group, flags, f"b{bits} g{group} f{flags}")
 
 
@@ -122,7 +122,7 @@ def _edge_groups(group):
 @pytest.mark.parametrize("group", [32, 64, 128, 256])
 def test_codec_edge_cases(bits, group):
     x = _edge_groups(group)
-    for flags in (SR, 0, SR | F32):
+    for flags in (SR, 0, SR | F32, SR | INT, INT):
         check_codec(x, bits, group, flags, f"edge b{bits} g{group} f{flags}")
 
 
@@ -152,6 +152,9 @@ def test_every_scale_value(bits):
     x = W.f32_to_bf16_bits((hf[:, None] * frac[None, :]).astype(np.float32)).reshape(-1)
     check_codec(x, bits, 32, 0, f"scales b{bits}")
     check_codec(x, bits, 32, SR, f"scales sr b{bits}")
+    # the same sweep passes every decision point of the integer scale (Eq. 1)
+    check_codec(x, bits, 32, INT, f"scales int b{bits}")
+    check_codec(x, bits, 32, SR | INT, f"scales sr int b{bits}")
 
 
 # ---- reduce_requant -----------------------------------------------------------------------------------------------
@@ -179,6 +182,7 @@ def test_reduce_requant_all_formats(bits, group):
     xs = [W.tensor(2, p, rows=1, cols=n).reshape(-1) for p in range(8)]
     check_reduce(xs, bits, group, SR, f"b{bits} g{group} N8")
     check_reduce(xs[:3], bits, group, 0, f"b{bits} g{group} N3 no-sr")
+    check_reduce(xs[:5], bits, group, SR | INT, f"b{bits} g{group} N5 integer metadata")
 
 
 @pytest.mark.parametrize("n_peers", [1, 2, 5, 16])
@@ -187,6 +191,8 @@ def test_reduce_requant_peer_counts(n_peers):
     xs = [W.tensor(4, p, rows=1, cols=n).reshape(-1) for p in range(n_peers)]
     check_reduce(xs, 3, 128, SR, f"N{n_peers}")
     check_reduce(xs, 6, 64, SR | F32, f"N{n_peers} fp32 meta", flags_out=SR)
+    check_reduce(xs, 2, 32, SR | INT, f"N{n_peers} integer meta in, bf16 out", flags_out=SR)
+    check_reduce(xs, 4, 32, SR, f"N{n_peers} bf16 meta in, integer out", flags_out=SR | INT)
 
 
 @pytest.mark.parametrize("bits_in,bits_out", [(2, 8), (3, 5), (4, 3), (5, 2), (6, 7), (7, 4), (8, 6)])
@@ -196,6 +202,7 @@ def test_reduce_requant_other_output_width(bits_in, bits_out):
         xs = [W.tensor(2, p, rows=1, cols=n).reshape(-1) for p in range(5)]
         check_reduce(xs, bits_in, group, SR, f"in b{bits_in} out b{bits_out} g{group}", bits_out=bits_out)
     check_reduce(xs[:2], bits_in, 64, 0, f"in b{bits_in} out b{bits_out} no-sr", bits_out=bits_out, flags_out=F32)
+    check_reduce(xs[:3], bits_in, 32, SR | INT, f"in b{bits_in} out b{bits_out} integer meta", bits_out=bits_out)
 
 
 def test_reduce_requant_edge_cases():
@@ -204,6 +211,7 @@ def test_reduce_requant_edge_cases():
         xs = [base, base[::-1].copy(), np.roll(base, group)]
         check_reduce(xs, 4, group, SR, f"edge g{group}")
         check_reduce(xs, 2, group, SR, f"edge g{group} b2")
+        check_reduce(xs, 3, group, SR | INT, f"edge g{group} b3 integer meta")
 
 
 # ---- slices and the whole two-step AllReduce on one GPU (Sections 3.1, 3.4) ----------------------------------
@@ -292,7 +300,8 @@ def check_dispatch(x, ids, E, bits, group, flags, what):
         assert np.array_equal(got[:, off:off + size], send_o[:, off:off + size]), f"{what}: rows differ in {name}"
 
 
-@pytest.mark.parametrize("bits,group,flags", [(2, 128, SR), (3, 32, SR), (4, 64, 0), (5, 128, SR | F32), (7, 256, SR), (8, 128, SR)])
+@pytest.mark.parametrize("bits,group,flags", [(2, 128, SR), (3, 32, SR), (4, 64, 0), (5, 128, SR | F32), (7, 256, SR), (8, 128, SR),
+                                              (2, 32, SR | INT), (4, 128, INT)])
 def test_dispatch_quant_small(bits, group, flags):
     T, H, K, E = 300, 768, 4, 40  # slots not a multiple of the planning chunk, rows not a multiple of a block
     x = W.tensor(3, 0, rows=T, cols=H)
@@ -327,6 +336,13 @@ def test_workload2_full(bits):
     xs = [W.tensor(2, p).reshape(-1) for p in range(8)]
     check_codec(xs[0], bits, 128, SR, f"workload 2 b{bits}")
     check_reduce(xs, bits, 128, SR, f"workload 2 b{bits} N8")
+
+
+def test_workload2_paper_default_low_bit_shape():
+    """Section 4.1's default for INT2: groups of 32, spike reserving, integer scale and zero (Eq. 1, Table 4)."""
+    xs = [W.tensor(2, p).reshape(-1) for p in range(8)]
+    check_codec(xs[0], 2, 32, SR | INT, "workload 2 b2 g32 integer meta")
+    check_reduce(xs, 2, 32, SR | INT, "workload 2 b2 g32 integer meta N8")
 
 
 def test_workload3_full():
