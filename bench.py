@@ -29,9 +29,10 @@ TRAFFIC_BYTES = {"quantize_pack": 41.34e6, "reduce_requant": 74.87e6, "unpack_de
 VALU_OPS_PER_ELEMENT = {"quantize_pack": 18.0, "reduce_requant": 68.3, "unpack_dequant": 6.4}
 
 
-def packed_bytes(n, bits, group, spike=True):
-    """Algorithmic size of a packed record: planes + per-group metadata (no alignment padding)."""
-    return n * bits // 8 + (10 if spike else 4) * (n // group)
+def packed_bytes(n, bits, group, spike=True, int_meta=False):
+    """Algorithmic size of a packed record: planes + per-group metadata (no alignment padding).  Per group:
+    scale + zero (2 x 2 bytes, 2 x 1 with the integer metadata of Eq. 1) and, with spike reserving, 2 x (2 + 1)."""
+    return n * bits // 8 + ((2 if int_meta else 4) + (6 if spike else 0)) * (n // group)
 
 
 def main():
@@ -70,21 +71,21 @@ def main():
     def ev():
         return torch.cuda.Event(enable_timing=True)
 
-    def make_sets(bits, n_sets):
+    def make_sets(bits, n_sets, group=group, flags=SR):
         """n_sets independent copies of (x, 8 packed peers, outputs) at different addresses."""
-        L = fcv2.get_layout(n, bits, group, SR)
+        L = fcv2.get_layout(n, bits, group, flags)
         sets = []
         for _ in range(n_sets):
-            peers = [fcv2.quantize_pack(x, bits, group, SR) for x in xs]
-            sets.append(dict(x=xs[0].clone(), peers=peers,
+            peers = [fcv2.quantize_pack(x, bits, group, flags) for x in xs]
+            sets.append(dict(x=xs[0].clone(), peers=peers, group=group, flags=flags,
                              q=torch.zeros(L.total_bytes, dtype=torch.uint8, device=dev),
                              r=torch.zeros(L.total_bytes, dtype=torch.uint8, device=dev),
                              o=torch.empty(n, dtype=torch.bfloat16, device=dev)))
         torch.cuda.synchronize()
         return sets
 
-    def algo_bytes(bits):
-        P = packed_bytes(n, bits, group)
+    def algo_bytes(bits, group=group, int_meta=False):
+        P = packed_bytes(n, bits, group, True, int_meta)
         return dict(quantize_pack=2 * n + P, reduce_requant=(n_peers + 1) * P, unpack_dequant=P + 2 * n)
 
     def n_sets_for(bits):
@@ -95,10 +96,10 @@ def main():
         """Arguments marshalled once per buffer set: a timed loop is C-ABI calls and nothing else."""
         import ctypes as C
         lib = fcv2.lib()
-        fmt = fcv2._Fmt(bits, group, SR)
         stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
         for s in sets:
             if s.get("bits") != bits:
+                fmt = fcv2._Fmt(bits, s["group"], s["flags"])
                 arr = (C.c_void_p * n_peers)(*[p.data_ptr() for p in s["peers"]])
                 s["bits"] = bits
                 s["keep"] = (arr, fmt)
@@ -227,14 +228,31 @@ def main():
         del bufs, x3
         torch.cuda.empty_cache()
 
+    # ---- the paper's default shape for the low widths (Section 4.1): groups of 32, spike reserving, and the integer
+    # ---- scale and zero of Eq. 1 (Table 4, second row) against bf16 metadata ------------------------------------------
+    low_bit = {}
+    if not args.no_sweep:
+        for b in (2, 3, 4):
+            for name, fl, im in (("bf16_meta", SR, False), ("int_meta", SR | fcv2.F_META_INT, True)):
+                per_set = 2 * n * 2 + (n_peers + 2) * packed_bytes(n, b, 32, True, im)
+                s = make_sets(b, max(4, -(-3 * LLC_BYTES // per_set)), 32, fl)
+                k_b = run_kernels(s, b, max(10, args.steps // 2), 3)
+                abb = algo_bytes(b, 32, im)
+                low_bit[f"b{b}_g32_{name}"] = dict(
+                    record_bytes=packed_bytes(n, b, 32, True, im),
+                    **{k: dict(us=round(k_b[k] * 1e3, 2), gbs=round(abb[k] / (k_b[k] * 1e-3) / 1e9, 1)) for k in abb})
+                del s
+                torch.cuda.empty_cache()
+
     # ---- quality proxy: signal-to-quantization-noise of plain RTN against spike reserving (direction of Tables 3, 7, 8) --
     quality = {}
     if not args.no_sweep:
         xf = xs[0].float()
         for b in (2, 3, 4, 5, 6, 8):
             row = {}
-            for name, fl in (("rtn", 0), ("spike_reserving", SR)):
-                v = fcv2.unpack_dequant(fcv2.quantize_pack(xs[0], b, group, fl), n, b, group, fl, torch.float32)
+            for name, fl, g in (("rtn", 0, group), ("spike_reserving", SR, group), ("g32_spike_reserving", SR, 32),
+                                ("g32_spike_reserving_int_meta", SR | fcv2.F_META_INT, 32)):
+                v = fcv2.unpack_dequant(fcv2.quantize_pack(xs[0], b, g, fl), n, b, g, fl, torch.float32)
                 row[name + "_sqnr_db"] = round(float(10 * torch.log10(xf.pow(2).sum() / (v - xf).pow(2).sum())), 2)
             quality[str(b)] = row
         del xf
@@ -350,7 +368,7 @@ def main():
         "warm_cache_gbs": round(total_bytes / (ms_warm * 1e-3) / 1e9, 1),
         "copy_ceiling_gbs": round(copy_gbs, 1),
         "kernels": kernels, "roofline": roofline, "alu_roofline": alu, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
-        "quality_proxy_sqnr_g128": quality, "two_step_allreduce_rank_share": two_step, "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
+        "quality_proxy_sqnr": quality, "low_bit_default_shape_g32": low_bit, "two_step_allreduce_rank_share": two_step, "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
     }
     print(json.dumps(out))
 

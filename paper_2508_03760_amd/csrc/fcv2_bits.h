@@ -126,6 +126,30 @@ FCV2_D ScaleInt scale_int_of(float s) {
     return r;
 }
 
+// The same two functions from per-code tables (the kernels keep them in LDS): pow_tab[k + 129] = 2^(k/10) for
+// k = -128..127 (entries 0 and 257 are never selected, they only keep the neighbour reads in bounds),
+// thr_tab[k + 128] = smallest fp32 whose code is >= k, for k = -128..128.  Entry t of each:
+FCV2_D float scale_table_pow(int t) { return (t >= 1 && t <= 256) ? scale_of_int(t - 129) : 0.0f; }
+FCV2_D float scale_table_thr(int t) {
+    int e, j;
+    split_tenths(t - 128, e, j);  // the split also holds for k = 128
+    return ldexpf(kThr10th[j], e);
+}
+constexpr int kScaleTablePow = 258, kScaleTableThr = 257;
+
+FCV2_D ScaleInt scale_int_from_tables(float s, const float* pow_tab, const float* thr_tab) {
+    const int k0 = (s > 0.0f) ? scale_int_estimate(s) : -128;
+    const float below = thr_tab[k0 + 128], above = thr_tab[k0 + 129];
+    int d = 0;
+    if (s >= above) d = 1;
+    if (s < below) d = -1;
+    if (k0 + d > 127 || k0 + d < -128) d = 0;
+    ScaleInt r;
+    r.k = k0 + d;
+    r.s = pow_tab[k0 + 129 + d];
+    return r;
+}
+
 // ---- codes (one per byte) -> planes ---------------------------------------------------------------------------
 // Field (code >> SH) & (2^W - 1) of each byte, moved to the top W bits of that byte.
 template <int W, int SH, int BITS> FCV2_HD uint32_t top_align(uint32_t c) {

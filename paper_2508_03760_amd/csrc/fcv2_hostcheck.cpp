@@ -101,6 +101,20 @@ void hc_scale_int_of(uint32_t first_bits, uint32_t count, int8_t* k, uint32_t* s
         memcpy(&s_bits[i], &r.s, 4);
     }
 }
+// The same through the per-code tables.
+void hc_scale_int_from_tables(uint32_t first_bits, uint32_t count, int8_t* k, uint32_t* s_bits) {
+    static float pow_tab[kScaleTablePow], thr_tab[kScaleTableThr];
+    for (int t = 0; t < kScaleTablePow; ++t) pow_tab[t] = scale_table_pow(t);
+    for (int t = 0; t < kScaleTableThr; ++t) thr_tab[t] = scale_table_thr(t);
+    for (uint32_t i = 0; i < count; ++i) {
+        const uint32_t b = first_bits + i;
+        float f;
+        memcpy(&f, &b, 4);
+        const ScaleInt r = scale_int_from_tables(f, pow_tab, thr_tab);
+        k[i] = (int8_t)r.k;
+        memcpy(&s_bits[i], &r.s, 4);
+    }
+}
 int hc_scale_int_estimate(float s) { return scale_int_estimate(s); }
 float hc_scale_of_int(int k) { return scale_of_int(k); }
 

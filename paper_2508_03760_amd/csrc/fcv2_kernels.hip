@@ -45,6 +45,19 @@ struct GroupMeta {
 // How scale and zero are stored.
 constexpr uint32_t kMetaBf16 = 0, kMetaFp32 = 1, kMetaInt = 2;
 
+// Integer metadata: per-block LDS tables of 2^(k/10) and of the decision points of Eq. 1, one entry per code, so
+// that coding and decoding a scale are table reads.  Called by all threads of a 256-thread block, before any of
+// them leaves the kernel; tabs holds kScaleTablePow + kScaleTableThr floats.
+constexpr int kScaleTables = kScaleTablePow + kScaleTableThr;
+__device__ __forceinline__ void fill_scale_tables(float* tabs) {
+    const int t = (int)threadIdx.x;
+    tabs[t] = scale_table_pow(t);
+    tabs[kScaleTablePow + t] = scale_table_thr(t);
+    if (t < kScaleTablePow - 256) tabs[256 + t] = scale_table_pow(256 + t);
+    if (t < kScaleTableThr - 256) tabs[kScaleTablePow + 256 + t] = scale_table_thr(256 + t);
+    __syncthreads();
+}
+
 // ---- cross-lane helpers -------------------------------------------------------------------------------------
 template <int CTRL> __device__ __forceinline__ uint32_t dpp(uint32_t v) {
     // old = identity of the unsigned minimum: the move folds into v_min_u32_dpp
@@ -128,8 +141,8 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // the two smallest composites (key << 16 | position) and the two smallest of (~key << 16 | position) are
 // tracked in one pass; the smallest of each gives a spike and its position, the second the new range.
 template <int BITS, int EPL, int LPG, bool SR>
-__device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint32_t lig, uint32_t mode, uint32_t (&c)[EPL / 4],
-                                              GroupMeta& m) {
+__device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint32_t lig, uint32_t mode, const float* tabs,
+                                              uint32_t (&c)[EPL / 4], GroupMeta& m) {
     const uint32_t lbase = lig * (uint32_t)EPL;
     uint32_t a1, a2, b1, b2;  // two smallest composites (a: minimum side, b: maximum side)
 #pragma unroll
@@ -186,7 +199,7 @@ __device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint
     if (mode == kMetaInt) {
         // Eq. 1: byte-sized scale and zero-point over the range widened to contain 0
         const float lo0 = (lo < 0.0f) ? lo : 0.0f, hi0 = (hi > 0.0f) ? hi : 0.0f;
-        const ScaleInt si = scale_int_of(div_by_qmax<QMAX>(__fsub_rn(hi0, lo0)));
+        const ScaleInt si = scale_int_from_tables(div_by_qmax<QMAX>(__fsub_rn(hi0, lo0)), tabs, tabs + kScaleTablePow);
         s = si.s;  // in [2^-12.8, 2^12.7]
         inv = rcp_newton(s);
         raw_z = __builtin_amdgcn_cvt_pk_u8_f32(__fmul_rn(-lo0, inv), 0, 0u);  // nearest even, saturated to [0, 255]
@@ -429,12 +442,12 @@ template <int LPG, bool SR> __device__ __forceinline__ MetaOffsets meta_offsets(
     return o;
 }
 
-template <bool SR, bool INT_META> __device__ __forceinline__ GroupMeta spread_meta(uint32_t raw, const MetaOffsets& o) {
+template <bool SR, bool INT_META> __device__ __forceinline__ GroupMeta spread_meta(uint32_t raw, const MetaOffsets& o, const float* tabs) {
     const uint32_t val = raw >> o.shift;
     GroupMeta m;
     const uint32_t sb = quad_bcast<0>(val), zb = quad_bcast<1>(val);
     if (INT_META) {  // Eq. 1 inverted: 2^(scale_int / 10), offset = -(zero * scale)
-        m.s = scale_of_int((int)(int8_t)(sb & 0xFFu));
+        m.s = tabs[((sb & 0xFFu) ^ 0x80u) + 1u];  // entry k + 129 of the table of 2^(k/10)
         m.lo = -__fmul_rn((float)(zb & 0xFFu), m.s);
     } else {
         m.s = u2f(sb << o.to_f32);
@@ -508,6 +521,8 @@ __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restr
     // apart); slice_lanes is a multiple of 64 then, so a wave's tile lies in one slice.  One slice: slice_lanes = n_lanes.
     constexpr int EPL = kEplStream;
     __shared__ uint4 lds[kWaves][64 * kRowU4];
+    __shared__ float tabs[kScaleTables];
+    if (meta_mode == kMetaInt) fill_scale_tables(tabs);
     const uint32_t lane = threadIdx.x & 63;
     const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));  // uniform: tiles are per wave
     const uint32_t lig = lane & (LPG - 1);
@@ -524,7 +539,7 @@ __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restr
         if (L < n_lanes) {  // groups never straddle the end: whole groups are in or out together
             uint32_t c[EPL / 4];
             GroupMeta m;
-            quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode, c, m);
+            quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode, tabs, c, m);
             uint8_t* o = out + slice * record_stride;
             const uint32_t Lr = L - slice * slice_lanes;  // lane inside the record
             store_planes<BITS, EPL>(o, rec, Lr, c);
@@ -689,6 +704,8 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n
                                                            uint32_t meta_mode_in, uint32_t meta_mode_out) {
     constexpr int ROW = EPL / 4 + 1;  // uint4 per private patch row, one of padding: conflict-free 16-byte accesses
     __shared__ uint4 lds[kBlock * ROW];
+    __shared__ float tabs[kScaleTables];
+    if (meta_mode_in == kMetaInt || meta_mode_out == kMetaInt) fill_scale_tables(tabs);
     const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
     if (L >= n_lanes) return;
     const uint32_t lig = threadIdx.x & (LPG - 1);
@@ -702,7 +719,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n
     auto sum_peers = [&](auto int_meta) {
         constexpr bool INT_META = decltype(int_meta)::value;
         auto add_peer = [&](const RawPlanes<EPL>& r, uint32_t mraw) {
-            const GroupMeta m = spread_meta<SR, INT_META>(mraw, mo);
+            const GroupMeta m = spread_meta<SR, INT_META>(mraw, mo, tabs);
             float v[EPL];
             dequant_mix<BITS, EPL>(r, m.s, m.lo, v);
             if (SR) patch_spikes<EPL>(m, lig, row, v);
@@ -742,7 +759,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n
     for (int d = 0; d < EPL / 2; ++d) w[d] = pack_bf16(acc[2 * d], acc[2 * d + 1]);
     uint32_t c[EPL / 4];
     GroupMeta m;
-    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode_out, c, m);
+    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode_out, tabs, c, m);
     store_planes<BITS, EPL>(out, rec_out, L, c);
     if (lig == 0) store_meta<SR>(out, rec_out, L / LPG, m, meta_mode_out);
 }
@@ -757,6 +774,8 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
                                                                  uint32_t meta_mode_out) {
     constexpr int ROW = EPL / 4 + 1;
     __shared__ uint4 lds[kBlock * ROW];
+    __shared__ float tabs[kScaleTables];
+    if (meta_mode_in == kMetaInt || meta_mode_out == kMetaInt) fill_scale_tables(tabs);
     const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
     if (L >= n_lanes) return;
     const uint32_t lig = threadIdx.x & (LPG - 1);
@@ -768,7 +787,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
     for (int p = 0; p < n_peers; ++p) {
         const uint8_t* base = peers.base[p];
         const uint32_t mraw = *reinterpret_cast<const uint32_t*>(at32(base, mo.at));
-        const GroupMeta m = (meta_mode_in == kMetaInt) ? spread_meta<SR, true>(mraw, mo) : spread_meta<SR, false>(mraw, mo);
+        const GroupMeta m = (meta_mode_in == kMetaInt) ? spread_meta<SR, true>(mraw, mo, tabs) : spread_meta<SR, false>(mraw, mo, tabs);
         float v[EPL];
         switch (bits_in) {
 #define FCV2_CASE(B)                                                      \
@@ -801,7 +820,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
     for (int d = 0; d < EPL / 2; ++d) w[d] = pack_bf16(acc[2 * d], acc[2 * d + 1]);
     uint32_t c[EPL / 4];
     GroupMeta m;
-    quantize_lane<BITS_OUT, EPL, LPG, SR>(w, lig, meta_mode_out, c, m);
+    quantize_lane<BITS_OUT, EPL, LPG, SR>(w, lig, meta_mode_out, tabs, c, m);
     store_planes<BITS_OUT, EPL>(out, rec_out, L, c);
     if (lig == 0) store_meta<SR>(out, rec_out, L / LPG, m, meta_mode_out);
 }
@@ -932,6 +951,8 @@ __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __rest
                                                              Rec rec, uint32_t row_bytes, uint32_t meta_mode) {
     constexpr int EPL = kEplStream;
     __shared__ uint4 lds[kWaves][64 * kRowU4];
+    __shared__ float tabs[kScaleTables];
+    if (meta_mode == kMetaInt) fill_scale_tables(tabs);
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t lig = lane & (LPG - 1);
     const uint32_t tile = blockIdx.x * kWaves + wave;
@@ -945,7 +966,7 @@ __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __rest
     const uint32_t r = L - t * lanes_per_row;  // lane inside the row
     uint32_t c[EPL / 4];
     GroupMeta m;
-    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode, c, m);
+    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode, tabs, c, m);
     const uint32_t g = r / LPG;
     // The send buffer is addressed with 32-bit offsets (checked on the host): a row's offset is one 24-bit multiply,
     // every store one add on top of per-lane offsets computed once.

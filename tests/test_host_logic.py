@@ -33,6 +33,8 @@ def hc():
         getattr(L, f).argtypes = [C.c_uint32]
     L.hc_scale_int_of.restype = None
     L.hc_scale_int_of.argtypes = [C.c_uint32, C.c_uint32, C.POINTER(C.c_int8), C.POINTER(C.c_uint32)]
+    L.hc_scale_int_from_tables.restype = None
+    L.hc_scale_int_from_tables.argtypes = L.hc_scale_int_of.argtypes
     L.hc_scale_int_estimate.restype = C.c_int
     L.hc_scale_int_estimate.argtypes = [C.c_float]
     L.hc_scale_of_int.restype = C.c_float
@@ -166,10 +168,11 @@ def test_short_division_is_ieee_division(hc, qmax):
 
 # ---- integer scale (Eq. 1) as the kernels compute it: table thresholds instead of a logarithm -------------------------
 
-def _scale_int_block(hc, first_bits, count):
+def _scale_int_block(hc, first_bits, count, tables=False):
     k = np.zeros(count, np.int8)
     sb = np.zeros(count, np.uint32)
-    hc.hc_scale_int_of(first_bits, count, k.ctypes.data_as(C.POINTER(C.c_int8)), sb.ctypes.data_as(C.POINTER(C.c_uint32)))
+    fn = hc.hc_scale_int_from_tables if tables else hc.hc_scale_int_of
+    fn(first_bits, count, k.ctypes.data_as(C.POINTER(C.c_int8)), sb.ctypes.data_as(C.POINTER(C.c_uint32)))
     return k, sb.view(np.float32)
 
 
@@ -186,6 +189,8 @@ def test_scale_int_every_significand(hc, exponent):
     assert np.array_equal(k[far].astype(np.float64), want[far])
     assert np.all(np.abs(k.astype(np.float64) - want) <= 1)
     assert np.array_equal(s, np.exp2(k.astype(np.float64) / 10.0).astype(np.float32))
+    k2, s2 = _scale_int_block(hc, first, 1 << 23, tables=True)  # the table form the kernels keep in LDS
+    assert np.array_equal(k, k2) and np.array_equal(s, s2)
 
 
 def test_scale_int_estimate_is_within_one(hc):
@@ -198,8 +203,9 @@ def test_scale_int_estimate_is_within_one(hc):
 def test_scale_int_ends_and_specials(hc):
     for bits, want in ((0x00000000, -128), (0x00000001, -128), (0x007FFFFF, -128), (0x80000000, -128), (0xBF800000, -128),
                        (0x7FC00000, -128), (0x7F800000, 127), (0x7F7FFFFF, 127), (0x3F800000, 0), (0x40000000, 10)):
-        k, s = _scale_int_block(hc, bits, 1)
-        assert int(k[0]) == want, hex(bits)
-        assert s[0] == np.float32(2.0 ** (want / 10.0))
+        for tables in (False, True):
+            k, s = _scale_int_block(hc, bits, 1, tables)
+            assert int(k[0]) == want, hex(bits)
+            assert s[0] == np.float32(2.0 ** (want / 10.0))
     for kk in range(-128, 128):
         assert np.float32(hc.hc_scale_of_int(kk)) == np.float32(np.exp2(np.float64(kk) / 10.0))
