@@ -317,6 +317,26 @@ def main():
             latency[str(b)] = {k: dict(us_per_call=round(timed(f, 1000, 20) * 1e3, 2)) for k, (f, _) in calls.items()}
             for k, (_, nbytes) in calls.items():
                 latency[str(b)][k]["gbs"] = round(nbytes / (latency[str(b)][k]["us_per_call"] * 1e-6) / 1e9, 1)
+            # the whole step (3 calls) eagerly and as a HIP graph of 20 recorded steps: launch overhead is what
+            # bounds this size, and the library is capturable (kernel launches only)
+            r5 = torch.zeros(L5.total_bytes, dtype=torch.uint8, device=dev)
+            arr5s = (C.c_void_p * 8)(q5.data_ptr(), *[p.data_ptr() for p in pk5[1:]])
+
+            def step5(st):
+                lib.fcv2_quantize_pack(C.c_void_p(x5.data_ptr()), n5, C.byref(fmt5), C.c_void_p(q5.data_ptr()), st)
+                lib.fcv2_reduce_requant(arr5s, 8, n5, C.byref(fmt5), C.byref(fmt5), C.c_void_p(r5.data_ptr()), None, st)
+                lib.fcv2_unpack_dequant(C.c_void_p(r5.data_ptr()), n5, C.byref(fmt5), C.c_void_p(o5.data_ptr()), fcv2.DT_BF16, st)
+
+            us_eager = timed(lambda i: step5(stream), 300, 20) * 1e3
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr):
+                cst = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+                for _ in range(20):
+                    step5(cst)
+            us_graph = timed(lambda i: gr.replay(), 30, 3) * 1e3 / 20
+            latency[str(b)]["step_eager_us"] = round(us_eager, 2)
+            latency[str(b)]["step_graph_us"] = round(us_graph, 2)
+            del gr
         del x5, peers5
         w4 = W.WORKLOADS[4]
         n4 = w4["rows"] * w4["cols"]
