@@ -292,6 +292,93 @@ def main():
         del send, mine, red, out_t, sbuf
         torch.cuda.empty_cache()
 
+    # ---- micro-chunk pipelining (Section 3.4) in its one-GPU form: the chunks' quantize -> reduce -> unpack chains
+    # ---- alternate between two streams, so one chunk's ramp-up and tail overlap the other's body ------------------------
+    pipelined = None
+    if not args.no_sweep:
+        import ctypes as C
+        lib = fcv2.lib()
+        f3 = fcv2._Fmt(3, group, SR)
+        n_chunks = 4
+        mc = n // n_chunks
+        Lc = fcv2.get_layout(mc, 3, group, SR)
+        oth = [[fcv2.quantize_pack(x[c * mc:(c + 1) * mc], 3, group, SR) for c in range(n_chunks)] for x in xs[1:]]
+        qc = [torch.zeros(Lc.total_bytes, dtype=torch.uint8, device=dev) for _ in range(n_chunks)]
+        rc_ = [torch.zeros(Lc.total_bytes, dtype=torch.uint8, device=dev) for _ in range(n_chunks)]
+        oc = torch.empty(n, dtype=torch.bfloat16, device=dev)
+        arrs = [(C.c_void_p * n_peers)(qc[c].data_ptr(), *[o[c].data_ptr() for o in oth]) for c in range(n_chunks)]
+        side = [torch.cuda.Stream(), torch.cuda.Stream()]
+        main = torch.cuda.current_stream()
+
+        def chunk_chain(c, st, xin):
+            h = C.c_void_p(st.cuda_stream)
+            lib.fcv2_quantize_pack(C.c_void_p(xin.data_ptr() + 2 * c * mc), mc, C.byref(f3), C.c_void_p(qc[c].data_ptr()), h)
+            lib.fcv2_reduce_requant(arrs[c], n_peers, mc, C.byref(f3), C.byref(f3), C.c_void_p(rc_[c].data_ptr()), None, h)
+            lib.fcv2_unpack_dequant(C.c_void_p(rc_[c].data_ptr()), mc, C.byref(f3), C.c_void_p(oc.data_ptr() + 2 * c * mc), fcv2.DT_BF16, h)
+
+        def serial_chunks(i):
+            for c in range(n_chunks):
+                chunk_chain(c, main, xs[i % n_peers])
+
+        def two_streams(i):
+            e = torch.cuda.Event()
+            e.record(main)
+            for c in range(n_chunks):
+                st = side[c % 2]
+                if c < 2:
+                    st.wait_event(e)
+                chunk_chain(c, st, xs[i % n_peers])
+            for st in side:
+                main.wait_stream(st)
+
+        # recorded as HIP graphs, so that host-side launch and event costs do not hide what the GPU does
+        def record(body):
+            body(0)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                body(0)
+            return g
+
+        def serial_in_capture(i):
+            cur = torch.cuda.current_stream()
+            for c in range(n_chunks):
+                chunk_chain(c, cur, xs[0])
+
+        def forked_in_capture(i):
+            cur = torch.cuda.current_stream()
+            for st in side:
+                st.wait_stream(cur)
+            for c in range(n_chunks):
+                chunk_chain(c, side[c % 2], xs[0])
+            for st in side:
+                cur.wait_stream(st)
+
+        def whole_in_capture(i):
+            cur = torch.cuda.current_stream()
+            h = C.c_void_p(cur.cuda_stream)
+            s0 = whole_set
+            lib.fcv2_quantize_pack(C.c_void_p(xs[0].data_ptr()), n, C.byref(f3), C.c_void_p(s0["q"].data_ptr()), h)
+            lib.fcv2_reduce_requant(s0["arr"], n_peers, n, C.byref(f3), C.byref(f3), C.c_void_p(s0["r"].data_ptr()), None, h)
+            lib.fcv2_unpack_dequant(C.c_void_p(s0["r"].data_ptr()), n, C.byref(f3), C.c_void_p(oc.data_ptr()), fcv2.DT_BF16, h)
+
+        Lw = fcv2.get_layout(n, 3, group, SR)
+        wp = [fcv2.quantize_pack(x, 3, group, SR) for x in xs]
+        whole_set = dict(q=torch.zeros(Lw.total_bytes, dtype=torch.uint8, device=dev), r=torch.zeros(Lw.total_bytes, dtype=torch.uint8, device=dev))
+        whole_set["arr"] = (C.c_void_p * n_peers)(whole_set["q"].data_ptr(), *[p.data_ptr() for p in wp[1:]])
+        cnt = max(20, args.steps // 2)
+        graphs = {k: record(f) for k, f in (("whole_payload", whole_in_capture), ("serial_chunks", serial_in_capture),
+                                            ("two_streams", forked_in_capture))}
+        pipelined = dict(chunks=n_chunks, chunk_elements=mc,
+                         **{k + "_us": round(timed(lambda i, g=g: g.replay(), cnt, 3) * 1e3, 2) for k, g in graphs.items()},
+                         eager_serial_chunks_us=round(timed(serial_chunks, cnt, 3) * 1e3, 2),
+                         eager_two_streams_us=round(timed(two_streams, cnt, 3) * 1e3, 2),
+                         note="one rank's quantize -> reduce(8) -> unpack on the 16M payload, whole or as 4 chunks; graph replays "
+                              "of one fixed buffer set (cache-warm), so compare the three graph figures with each other only")
+        del graphs, wp, whole_set
+        del oth, qc, rc_, oc
+        torch.cuda.empty_cache()
+
     # ---- decode-sized latency case (workload 5) and the large AllReduce payload (workload 4) --------------------
     latency, large = {}, {}
     if not args.no_sweep:
@@ -388,7 +475,7 @@ def main():
         "warm_cache_gbs": round(total_bytes / (ms_warm * 1e-3) / 1e9, 1),
         "copy_ceiling_gbs": round(copy_gbs, 1),
         "kernels": kernels, "roofline": roofline, "alu_roofline": alu, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
-        "quality_proxy_sqnr": quality, "low_bit_default_shape_g32": low_bit, "two_step_allreduce_rank_share": two_step, "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
+        "quality_proxy_sqnr": quality, "low_bit_default_shape_g32": low_bit, "two_step_allreduce_rank_share": two_step, "micro_chunk_pipelining": pipelined, "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
     }
     print(json.dumps(out))
 

@@ -285,6 +285,42 @@ def test_two_step_allreduce_on_one_gpu(bits):
     assert np.all(np.abs(got - exact) <= bound)
 
 
+def test_micro_chunks_on_two_streams_match_the_whole_payload():
+    """Section 3.4 cuts the payload into micro-chunks and overlaps their stages.  On one GPU: the chunks' quantize ->
+    reduce -> unpack chains alternate between two streams.  Groups never straddle a chunk, so the pipelined result
+    is bit-identical to processing the whole payload at once, and to the oracle's."""
+    N, C, group, bits = 4, 4, 128, 3
+    fmt = (bits, group, SR)
+    n = C * 2048 * 3
+    m = n // C
+    xs = [W.tensor(2, p, rows=1, cols=n).reshape(-1) for p in range(N)]
+    xd = to_dev_bf16(xs[0])
+    others = [[fcv2.quantize_pack(to_dev_bf16(x[c * m:(c + 1) * m]), *fmt) for c in range(C)] for x in xs[1:]]
+    L = fcv2.get_layout(m, *fmt)
+    q = [torch.zeros(L.total_bytes, dtype=torch.uint8, device=DEV) for _ in range(C)]
+    r = [torch.zeros(L.total_bytes, dtype=torch.uint8, device=DEV) for _ in range(C)]
+    out = torch.empty(n, dtype=torch.bfloat16, device=DEV)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]  # default priority
+    start = torch.cuda.Event()
+    start.record()
+    for c in range(C):
+        st = streams[c % 2]
+        st.wait_event(start)
+        with torch.cuda.stream(st):
+            fcv2.quantize_pack(xd[c * m:(c + 1) * m], *fmt, out=q[c])
+            fcv2.reduce_requant([q[c]] + [o[c] for o in others], m, fmt, out=r[c])
+            fcv2.unpack_dequant(r[c], m, *fmt, torch.bfloat16, out=out[c * m:(c + 1) * m])
+    for st in streams:
+        torch.cuda.current_stream().wait_stream(st)
+    torch.cuda.synchronize()
+    # the whole payload at once
+    whole = fcv2.unpack_dequant(fcv2.reduce_requant([fcv2.quantize_pack(to_dev_bf16(x), *fmt) for x in xs], n, fmt), n, *fmt,
+                                torch.bfloat16)
+    assert torch.equal(out.view(torch.int16), whole.view(torch.int16))
+    want = O.unpack_dequant(O.reduce_requant([O.quantize_pack(x, *fmt) for x in xs], n, fmt), n, *fmt, O.DT_BF16)
+    assert np.array_equal(out.view(torch.int16).cpu().numpy().view(np.uint16), want)
+
+
 # ---- dispatch_quant -------------------------------------------------------------------------------------------------
 
 def check_dispatch(x, ids, E, bits, group, flags, what):
