@@ -29,6 +29,7 @@ namespace fcv2 {
 
 struct Rec {  // section offsets of one packed record, relative to its first byte (records are < 4 GiB)
     uint32_t plane8, plane4, plane2, plane1, scale, zero, spike_val, spike_idx;
+    uint32_t total;  // bytes of the record
 };
 
 struct PeerPtrs {
@@ -336,24 +337,58 @@ __device__ __forceinline__ const uint8_t* at32(const uint8_t* __restrict__ base,
     return base + off;
 }
 
+// Two ways to read a record.  GlobalSrc: plain global loads from base + offset.  BufferSrc: buffer loads through a
+// resource descriptor (base, size) held in scalar registers; the 32-bit lane offset goes into the instruction as it
+// is, so a loop over many records needs no per-record address arithmetic in vector registers, and reads past the
+// record's size return 0 instead of touching memory.
+struct GlobalSrc {
+    const uint8_t* __restrict__ base;
+};
+struct BufferSrc {
+    __amdgpu_buffer_rsrc_t rsrc;
+};
+__device__ __forceinline__ BufferSrc buffer_src(const uint8_t* base, uint32_t bytes) {
+    BufferSrc b;
+    b.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(base), 0, (int)bytes, 0x00020000);  // raw 32-bit data
+    return b;
+}
+__device__ __forceinline__ uint4 ld128(const GlobalSrc& s, uint32_t off) { return *reinterpret_cast<const uint4*>(at32(s.base, off)); }
+__device__ __forceinline__ uint2 ld64(const GlobalSrc& s, uint32_t off) { return *reinterpret_cast<const uint2*>(at32(s.base, off)); }
+__device__ __forceinline__ uint32_t ld32(const GlobalSrc& s, uint32_t off) { return *reinterpret_cast<const uint32_t*>(at32(s.base, off)); }
+__device__ __forceinline__ uint32_t ld16(const GlobalSrc& s, uint32_t off) { return *reinterpret_cast<const uint16_t*>(at32(s.base, off)); }
+__device__ __forceinline__ uint32_t ld8(const GlobalSrc& s, uint32_t off) { return *at32(s.base, off); }
+__device__ __forceinline__ uint4 ld128(const BufferSrc& s, uint32_t off) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(s.rsrc, (int)off, 0, 0);
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 ld64(const BufferSrc& s, uint32_t off) {
+    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(s.rsrc, (int)off, 0, 0);
+    return make_uint2(v.x, v.y);
+}
+__device__ __forceinline__ uint32_t ld32(const BufferSrc& s, uint32_t off) { return __builtin_amdgcn_raw_buffer_load_b32(s.rsrc, (int)off, 0, 0); }
+__device__ __forceinline__ uint32_t ld16(const BufferSrc& s, uint32_t off) { return __builtin_amdgcn_raw_buffer_load_b16(s.rsrc, (int)off, 0, 0); }
+__device__ __forceinline__ uint32_t ld8(const BufferSrc& s, uint32_t off) { return __builtin_amdgcn_raw_buffer_load_b8(s.rsrc, (int)off, 0, 0); }
+
 // Plane pieces of one lane: EPL elements.
 template <int EPL> struct RawPlanes {
     uint32_t p8[EPL / 4], p4[EPL / 8], p2[(EPL + 15) / 16], p1;
 };
 
-template <int BITS, int EPL> __device__ __forceinline__ RawPlanes<EPL> load_planes(const uint8_t* __restrict__ base, const Rec& r, uint32_t L) {
+template <int BITS, int EPL, class SRC> __device__ __forceinline__ RawPlanes<EPL> load_planes(const SRC& src, const Rec& r, uint32_t L) {
     using P = Planes<BITS>;
     RawPlanes<EPL> o = {};
     if (P::w8) {
-        const uint8_t* at = at32(base, r.plane8 + (uint32_t)EPL * L);
+        const uint32_t at = r.plane8 + (uint32_t)EPL * L;
         if (EPL == 8) {
-            const uint2 v = *reinterpret_cast<const uint2*>(at);
+            const uint2 v = ld64(src, at);
             o.p8[0] = v.x;
             o.p8[1] = v.y;
         } else {
 #pragma unroll
             for (int i = 0; i < EPL / 16; ++i) {
-                const uint4 v = reinterpret_cast<const uint4*>(at)[i];
+                const uint4 v = ld128(src, at + 16u * i);
                 o.p8[4 * i] = v.x;
                 o.p8[4 * i + 1] = v.y;
                 o.p8[4 * i + 2] = v.z;
@@ -362,15 +397,15 @@ template <int BITS, int EPL> __device__ __forceinline__ RawPlanes<EPL> load_plan
         }
     }
     if (P::w4) {
-        const uint8_t* at = at32(base, r.plane4 + (uint32_t)(EPL / 2) * L);
-        if (EPL == 8) o.p4[0] = *reinterpret_cast<const uint32_t*>(at);
+        const uint32_t at = r.plane4 + (uint32_t)(EPL / 2) * L;
+        if (EPL == 8) o.p4[0] = ld32(src, at);
         if (EPL == 16) {
-            const uint2 v = *reinterpret_cast<const uint2*>(at);
+            const uint2 v = ld64(src, at);
             o.p4[0] = v.x;
             o.p4[EPL / 8 - 1] = v.y;
         }
         if (EPL == 32) {
-            const uint4 v = *reinterpret_cast<const uint4*>(at);
+            const uint4 v = ld128(src, at);
             o.p4[0] = v.x;
             o.p4[1 % (EPL / 8)] = v.y;
             o.p4[2 % (EPL / 8)] = v.z;
@@ -378,20 +413,20 @@ template <int BITS, int EPL> __device__ __forceinline__ RawPlanes<EPL> load_plan
         }
     }
     if (P::w2) {
-        const uint8_t* at = at32(base, r.plane2 + (uint32_t)(EPL / 4) * L);
-        if (EPL == 8) o.p2[0] = *reinterpret_cast<const uint16_t*>(at);
-        if (EPL == 16) o.p2[0] = *reinterpret_cast<const uint32_t*>(at);
+        const uint32_t at = r.plane2 + (uint32_t)(EPL / 4) * L;
+        if (EPL == 8) o.p2[0] = ld16(src, at);
+        if (EPL == 16) o.p2[0] = ld32(src, at);
         if (EPL == 32) {
-            const uint2 v = *reinterpret_cast<const uint2*>(at);
+            const uint2 v = ld64(src, at);
             o.p2[0] = v.x;
             o.p2[(EPL + 15) / 16 - 1] = v.y;
         }
     }
     if (P::w1) {
-        const uint8_t* at = at32(base, r.plane1 + (uint32_t)(EPL / 8) * L);
-        if (EPL == 8) o.p1 = *at;
-        if (EPL == 16) o.p1 = *reinterpret_cast<const uint16_t*>(at);
-        if (EPL == 32) o.p1 = *reinterpret_cast<const uint32_t*>(at);
+        const uint32_t at = r.plane1 + (uint32_t)(EPL / 8) * L;
+        if (EPL == 8) o.p1 = ld8(src, at);
+        if (EPL == 16) o.p1 = ld16(src, at);
+        if (EPL == 32) o.p1 = ld32(src, at);
     }
     return o;
 }
@@ -588,7 +623,7 @@ __global__ __launch_bounds__(kBlock) void k_unpack_dequant_t(PeerPtrs records, u
         const uint8_t* __restrict__ in = records.base[slice];
         const uint32_t Lr = L - slice * slice_lanes;  // lane inside the record
         const uint32_t g = Lr / LPG;
-        const RawPlanes<EPL> r = load_planes<BITS, EPL>(in, rec, Lr);
+        const RawPlanes<EPL> r = load_planes<BITS, EPL>(GlobalSrc{in}, rec, Lr);
         float s, lo;
         if (meta_mode == kMetaInt) {
             s = scale_of_int((int)(int8_t)in[rec.scale + g]);
@@ -733,15 +768,17 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n
             uint32_t mraw[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                r[i] = load_planes<BITS, EPL>(peers.base[p + i], rec_in, L);
-                mraw[i] = *reinterpret_cast<const uint32_t*>(at32(peers.base[p + i], mo.at));
+                const BufferSrc src = buffer_src(peers.base[p + i], rec_in.total);
+                r[i] = load_planes<BITS, EPL>(src, rec_in, L);
+                mraw[i] = ld32(src, mo.at);
             }
 #pragma unroll
             for (int i = 0; i < 4; ++i) add_peer(r[i], mraw[i]);
         }
         for (; p < n_peers; ++p) {
-            const RawPlanes<EPL> r = load_planes<BITS, EPL>(peers.base[p], rec_in, L);
-            const uint32_t mraw = *reinterpret_cast<const uint32_t*>(at32(peers.base[p], mo.at));
+            const BufferSrc src = buffer_src(peers.base[p], rec_in.total);
+            const RawPlanes<EPL> r = load_planes<BITS, EPL>(src, rec_in, L);
+            const uint32_t mraw = ld32(src, mo.at);
             add_peer(r, mraw);
         }
     };
@@ -785,14 +822,14 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
 #pragma unroll
     for (int j = 0; j < EPL; ++j) acc[j] = -0.0f;
     for (int p = 0; p < n_peers; ++p) {
-        const uint8_t* base = peers.base[p];
-        const uint32_t mraw = *reinterpret_cast<const uint32_t*>(at32(base, mo.at));
+        const BufferSrc src = buffer_src(peers.base[p], rec_in.total);
+        const uint32_t mraw = ld32(src, mo.at);
         const GroupMeta m = (meta_mode_in == kMetaInt) ? spread_meta<SR, true>(mraw, mo, tabs) : spread_meta<SR, false>(mraw, mo, tabs);
         float v[EPL];
         switch (bits_in) {
 #define FCV2_CASE(B)                                                      \
     case B: {                                                             \
-        const RawPlanes<EPL> r = load_planes<B, EPL>(base, rec_in, L);    \
+        const RawPlanes<EPL> r = load_planes<B, EPL>(src, rec_in, L);     \
         dequant_mix<B, EPL>(r, m.s, m.lo, v);                             \
         break;                                                            \
     }
@@ -1048,6 +1085,7 @@ static Rec rec_of(const fcv2_layout_t& l) {
     r.zero = rel(l.off_zero);
     r.spike_val = rel(l.off_spike_val);
     r.spike_idx = rel(l.off_spike_idx);
+    r.total = (uint32_t)l.total_bytes;
     return r;
 }
 
