@@ -348,6 +348,27 @@ def test_dispatch_quant_small(bits, group, flags):
     check_dispatch(x, ids, E, bits, group, flags, f"dispatch b{bits} g{group}")
 
 
+@pytest.mark.parametrize("bits,group,flags", [(2, 128, SR), (3, 32, SR), (4, 64, 0), (5, 128, SR | F32), (6, 32, SR | INT), (7, 64, SR | INT),
+                                              (8, 128, SR), (2, 256, SR), (4, 128, SR | INT), (3, 256, F32), (8, 32, 0)])
+def test_dispatch_quant_rows_of_whole_kilo_blocks(bits, group, flags):
+    """Rows of whole 1024-element blocks (so wave tiles straddle tokens half-way), more formats, and a tensor that
+    ends in the middle of a wave."""
+    T, H, K, E = 37, 3072, 3, 11
+    x = W.tensor(3, 2, rows=T, cols=H)
+    ids = W.topk_routing(W.seed_for(3) + 1, T, E, K)
+    ids[4, 1] = -1
+    ids[T - 1, :] = -1
+    check_dispatch(x, ids, E, bits, group, flags, f"dispatch wide rows b{bits} g{group} f{flags}")
+
+
+def test_dispatch_quant_nine_copies_per_token():
+    T, H, K, E = 20, 1024, 9, 16  # more copies than one batch of destination loads
+    x = W.tensor(3, 3, rows=T, cols=H)
+    ids = W.topk_routing(W.seed_for(3) + 2, T, E, K)
+    check_dispatch(x, ids, E, 2, 128, SR, "dispatch K=9")
+    check_dispatch(x, ids, E, 5, 64, SR, "dispatch K=9 b5")
+
+
 def test_dispatch_quant_degenerate_routing():
     T, H, K, E = 130, 512, 8, 256
     x = W.tensor(3, 1, rows=T, cols=H)
