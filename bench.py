@@ -176,6 +176,14 @@ def main():
     ms_copy = timed(lambda i: fcv2.lib().fcv2_stream_copy(C.c_void_p(ca.data_ptr()), C.c_void_p(cb.data_ptr()), ca.numel(), cstream), 20, 3)
     copy_gbs = 2 * ca.numel() / (ms_copy * 1e-3) / 1e9
     del ca, cb
+    # the same copy kernel moving what quantize_pack / unpack_dequant move at the headline shape (41 MB): what a kernel
+    # of that size can reach at all, launch ramp and tail included
+    half = (ab["quantize_pack"] // 2 + 4095) // 4096 * 4096
+    csets = [(torch.empty(half, dtype=torch.uint8, device=dev), torch.empty(half, dtype=torch.uint8, device=dev)) for _ in range(14)]
+    ms_copy_small = timed(lambda i: fcv2.lib().fcv2_stream_copy(C.c_void_p(csets[i % 14][0].data_ptr()), C.c_void_p(csets[i % 14][1].data_ptr()),
+                                                               half, cstream), 56, 14)
+    copy_same_size = dict(bytes_moved=2 * half, us=round(ms_copy_small * 1e3, 2), gbs=round(2 * half / (ms_copy_small * 1e-3) / 1e9, 1))
+    del csets
     # warm-cache figure for context: one buffer set, everything stays in the last-level cache
     ms_warm = run_steps(sets[:1], bits, args.steps, args.warmup)
     del sets
@@ -497,7 +505,7 @@ def main():
                    "buffer_sets_rotated": n_sets_for(3)},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "warm_cache_gbs": round(total_bytes / (ms_warm * 1e-3) / 1e9, 1),
-        "copy_ceiling_gbs": round(copy_gbs, 1),
+        "copy_ceiling_gbs": round(copy_gbs, 1), "copy_same_size_as_quantize_pack": copy_same_size,
         "kernels": kernels, "roofline": roofline, "alu_roofline": alu, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
         "quality_proxy_sqnr": quality, "low_bit_default_shape_g32": low_bit, "two_step_allreduce_rank_share": two_step, "micro_chunk_pipelining": pipelined, "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
     }
