@@ -3,10 +3,11 @@
 // Work decomposition: a lane owns EPL consecutive elements, a quantization group of G elements is owned by
 // LPG = G/EPL neighbouring lanes, so group reductions are DPP butterflies inside a 16-lane row.  The kernels
 // that stream a tensor once (quantize_pack, unpack_dequant, dispatch_quant) use EPL = 32 (64 bytes of bf16 per
-// lane, LPG = 1..8): per-lane overheads are paid once per 32 elements and every wave keeps 4 KiB of loads in
-// flight.  reduce_requant uses EPL = 8 (LPG = 4..32): its values must be patched in registers at the spike
-// positions, which is cheapest when a lane seldom owns both spikes of a group.  The paper's own block shape
-// (512 threads x 8 values, Section 4.1) was made for other hardware and is not followed.
+// lane, LPG = 1..8): per-lane overheads are paid once per 32 elements, and a wave's tile of 2048 elements is moved
+// with coalesced 16-byte accesses and transposed through LDS.  reduce_requant uses EPL = 16 (8 for groups of 32, so
+// that a group still spans a quad): its accumulators and the values of one peer live in registers, and the spike
+// positions of every peer are patched through LDS.  The paper's own block shape (512 threads x 8 values,
+// Section 4.1) was made for other hardware and is not followed.
 //
 // Arithmetic is fixed so that results can be compared bit for bit with an independent CPU implementation:
 //   scale = (hi - lo) / qmax in fp32 (IEEE division), stored rounded up to bf16 unless FCV2_F_META_FP32;
