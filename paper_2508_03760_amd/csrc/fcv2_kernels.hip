@@ -138,12 +138,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 
 // ---- encoder core: EPL consecutive bf16 values of this lane -> EPL codes (one per byte) + the group's metadata ----
 // w[d] holds elements 2d (low half) and 2d+1 (high half).  lig = lane index inside the group (LPG = G / EPL lanes).
+// row = this lane's private LDS scratch (at least EPL bytes, 16-byte aligned), free at the time of the call.
 // Spike reserving (Section 3.3): the group's minimum and maximum are set aside (lowest index on ties, the
 // maximum searched among the other positions) and the rest is quantized over [2nd smallest, 2nd largest]:
 // the two smallest composites (key << 16 | position) and the two smallest of (~key << 16 | position) are
 // tracked in one pass; the smallest of each gives a spike and its position, the second the new range.
 template <int BITS, int EPL, int LPG, bool SR>
-__device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint32_t lig, uint32_t mode, const float* tabs,
+__device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint32_t lig, uint32_t mode, const float* tabs, uint4* row,
                                               uint32_t (&c)[EPL / 4], GroupMeta& m) {
     const uint32_t lbase = lig * (uint32_t)EPL;
     uint32_t a1, a2, b1, b2;  // two smallest composites (a: minimum side, b: maximum side)
@@ -153,7 +154,9 @@ __device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint
         const short2v sv = __builtin_bit_cast(short2v, w[d]);
         const uint32_t sign = __builtin_bit_cast(uint32_t, sv >> (short2v){15, 15});
         const uint32_t k = w[d] ^ (sign | 0x80008000u);  // two order keys
-        const uint32_t e0 = (k << 16) | (uint32_t)(2 * d), e1 = (k & 0xFFFF0000u) | (uint32_t)(2 * d + 1);
+        uint32_t e0 = (k << 16) | (uint32_t)(2 * d), e1 = (k & 0xFFFF0000u) | (uint32_t)(2 * d + 1);
+        FCV2_KEEP(e0);  // keeps each composite one shift-or / and-or instruction (no regrouping with the xor below)
+        FCV2_KEEP(e1);
         const uint32_t f0 = e0 ^ 0xFFFF0000u, f1 = e1 ^ 0xFFFF0000u;  // inverted key: min finds the largest value
         if (d == 0) {
             a1 = min(e0, e1);
@@ -252,19 +255,38 @@ __device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint
             c[i] = cc;
         }
     }
-    if (SR && mode == kMetaInt) {
-        const uint32_t rel = imin - lbase;  // position inside this lane, or >= EPL
-        const uint32_t clr = ~(0xFFu << ((rel & 3u) * 8u));
-        const uint32_t dw = rel >> 2;
-#pragma unroll
-        for (int i = 0; i < EPL / 4; ++i) c[i] &= (dw == (uint32_t)i) ? clr : 0xFFFFFFFFu;
-    }
     if (SR) {
-        const uint32_t rel = imax - lbase;  // position inside this lane, or >= EPL
-        const uint32_t clr = ~(0xFFu << ((rel & 3u) * 8u));
-        const uint32_t dw = rel >> 2;
+        // The codes at the spike positions are 0.  A position is a dynamic byte index into c[]: the owner lanes park
+        // c[] in their private LDS row, clear the byte there and read the row back (a select per register would cost
+        // three VALU operations per register for every lane).
+        const uint32_t relmax = imax - lbase;  // position inside this lane, or >= EPL
+        const uint32_t relmin = (mode == kMetaInt) ? imin - lbase : (uint32_t)EPL;
+        if (relmax < (uint32_t)EPL || relmin < (uint32_t)EPL) {
+            u32a* rw = reinterpret_cast<u32a*>(row);
+            uint8_t* rb = reinterpret_cast<uint8_t*>(row);
+            if (EPL >= 16) {
 #pragma unroll
-        for (int i = 0; i < EPL / 4; ++i) c[i] &= (dw == (uint32_t)i) ? clr : 0xFFFFFFFFu;
+                for (int i = 0; i < EPL / 16; ++i) row[i] = make_uint4(c[4 * i], c[4 * i + 1], c[4 * i + 2], c[4 * i + 3]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < EPL / 4; ++i) rw[i] = c[i];
+            }
+            if (relmax < (uint32_t)EPL) rb[relmax] = 0;
+            if (relmin < (uint32_t)EPL) rb[relmin] = 0;
+            if (EPL >= 16) {
+#pragma unroll
+                for (int i = 0; i < EPL / 16; ++i) {
+                    const uint4 v = row[i];
+                    c[4 * i] = v.x;
+                    c[4 * i + 1] = v.y;
+                    c[4 * i + 2] = v.z;
+                    c[4 * i + 3] = v.w;
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < EPL / 4; ++i) c[i] = rw[i];
+            }
+        }
     }
 }
 
@@ -575,7 +597,7 @@ __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restr
         if (L < n_lanes) {  // groups never straddle the end: whole groups are in or out together
             uint32_t c[EPL / 4];
             GroupMeta m;
-            quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode, tabs, c, m);
+            quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode, tabs, &lds[wave][lane * kRowU4], c, m);
             uint8_t* o = out + slice * record_stride;
             const uint32_t Lr = L - slice * slice_lanes;  // lane inside the record
             store_planes<BITS, EPL>(o, rec, Lr, c);
@@ -797,7 +819,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n
     for (int d = 0; d < EPL / 2; ++d) w[d] = pack_bf16(acc[2 * d], acc[2 * d + 1]);
     uint32_t c[EPL / 4];
     GroupMeta m;
-    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode_out, tabs, c, m);
+    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode_out, tabs, row, c, m);
     store_planes<BITS, EPL>(out, rec_out, L, c);
     if (lig == 0) store_meta<SR>(out, rec_out, L / LPG, m, meta_mode_out);
 }
@@ -858,7 +880,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
     for (int d = 0; d < EPL / 2; ++d) w[d] = pack_bf16(acc[2 * d], acc[2 * d + 1]);
     uint32_t c[EPL / 4];
     GroupMeta m;
-    quantize_lane<BITS_OUT, EPL, LPG, SR>(w, lig, meta_mode_out, tabs, c, m);
+    quantize_lane<BITS_OUT, EPL, LPG, SR>(w, lig, meta_mode_out, tabs, row, c, m);
     store_planes<BITS_OUT, EPL>(out, rec_out, L, c);
     if (lig == 0) store_meta<SR>(out, rec_out, L / LPG, m, meta_mode_out);
 }
@@ -1004,7 +1026,7 @@ __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __rest
     const uint32_t r = L - t * lanes_per_row;  // lane inside the row
     uint32_t c[EPL / 4];
     GroupMeta m;
-    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode, tabs, c, m);
+    quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode, tabs, &lds[wave][lane * kRowU4], c, m);
     const uint32_t g = r / LPG;
     // The send buffer is addressed with 32-bit offsets (checked on the host): a row's offset is one 24-bit multiply,
     // every store one add on top of per-lane offsets computed once.
