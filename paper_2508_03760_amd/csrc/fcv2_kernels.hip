@@ -477,13 +477,13 @@ template <int BITS, int EPL> __device__ __forceinline__ void unit_codes(const Ra
     }
 }
 
-// --- 8 elements per lane, metadata fetched by quads (used where the values are needed in registers) -----------
-// Everything a lane needs to read its 8 elements out of any record of one layout: byte offsets of the one
-// metadata item it fetches for its quad (lane & 3: scale, zero, spike values, spike indices), computed once and
-// reused for every peer.
+// --- metadata fetched by quads (reduce_requant) ---------------------------------------------------------------
+// Lane & 3 of every quad fetches one of the group's four metadata items (scale, zero, spike values, spike indices)
+// as the aligned dword that holds it; quad broadcasts hand the four to every lane.  Address and byte selector of
+// "its" item are computed once per lane and reused for every peer.
 struct MetaOffsets {
-    uint32_t at, shift;
-    uint32_t to_f32;  // left shift that turns a stored scale/zero into fp32 bits: 16 for bf16, 0 for fp32
+    uint32_t at;   // aligned dword that holds the item
+    uint32_t sel;  // byte selector (v_perm_b32) that moves the item to where its consumer wants it
 };
 
 template <int LPG, bool SR> __device__ __forceinline__ MetaOffsets meta_offsets(const Rec& r, uint32_t L, uint32_t mode) {
@@ -494,26 +494,32 @@ template <int LPG, bool SR> __device__ __forceinline__ MetaOffsets meta_offsets(
     if (SR && item == 2u) at = r.spike_val + 4u * g;
     if (SR && item == 3u) at = r.spike_idx + 2u * g;
     MetaOffsets o;
-    o.at = at & ~3u;                                 // aligned dword that holds the item
-    o.shift = (at & 3u) * 8u;
-    o.to_f32 = (mode == kMetaFp32) ? 0u : 16u;
+    o.at = at & ~3u;
+    // Selector bytes: 4 + k = byte k of the loaded dword, 0x0C = zero.
+    const uint32_t b0 = 4u + (at & 3u), b1 = b0 + 1u;
+    uint32_t sel = 0x07060504u;                                                      // fp32 items, spike values: as loaded
+    if (mode == kMetaBf16) sel = 0x00000C0Cu | (b0 << 16) | (b1 << 24);              // bf16 -> the upper half: fp32 bits
+    if (mode == kMetaInt) sel = 0x0C0C0C00u | b0;                                    // one byte -> the low byte
+    if (SR && item == 2u) sel = 0x07060504u;
+    if (SR && item == 3u) sel = 0x0C0C0000u | (b1 << 8) | b0;                        // two index bytes -> the low half
+    o.sel = sel;
     return o;
 }
 
 template <bool SR, bool INT_META> __device__ __forceinline__ GroupMeta spread_meta(uint32_t raw, const MetaOffsets& o, const float* tabs) {
-    const uint32_t val = raw >> o.shift;
+    const uint32_t val = __builtin_amdgcn_perm(raw, 0u, o.sel);
     GroupMeta m;
     const uint32_t sb = quad_bcast<0>(val), zb = quad_bcast<1>(val);
     if (INT_META) {  // Eq. 1 inverted: 2^(scale_int / 10), offset = -(zero * scale)
-        m.s = tabs[((sb & 0xFFu) ^ 0x80u) + 1u];  // entry k + 129 of the table of 2^(k/10)
-        m.lo = -__fmul_rn((float)(zb & 0xFFu), m.s);
+        m.s = tabs[(sb ^ 0x80u) + 1u];  // entry k + 129 of the table of 2^(k/10)
+        m.lo = -__fmul_rn((float)zb, m.s);
     } else {
-        m.s = u2f(sb << o.to_f32);
-        m.lo = u2f(zb << o.to_f32);
+        m.s = u2f(sb);
+        m.lo = u2f(zb);
     }
     m.raw_s = m.raw_z = 0;
     m.sv = SR ? quad_bcast<2>(val) : 0u;
-    m.si = SR ? (quad_bcast<3>(val) & 0xFFFFu) : 0u;
+    m.si = SR ? quad_bcast<3>(val) : 0u;
     return m;
 }
 
