@@ -577,10 +577,13 @@ __device__ __forceinline__ void tile_transpose(const TileIn& t, uint4* wave_lds,
 
 // Sender: persistent waves walk over the tiles; the next tile's loads are in flight while the current one is
 // quantized, so memory and arithmetic overlap inside every wave.
-template <int BITS, int LPG, bool SR>
+template <int BITS, int LPG, bool SR, bool INT_META>
 __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restrict__ x, uint32_t n_lanes, uint8_t* __restrict__ out,
-                                                            Rec rec, uint32_t meta_mode, uint32_t slice_lanes,
+                                                            Rec rec, uint32_t meta_mode_arg, uint32_t slice_lanes,
                                                             uint64_t record_stride) {
+    // The integer metadata path is a compile-time variant here: its tables and extra live values would otherwise
+    // cost the float formats a third of their registers (and with them two waves per SIMD).
+    const uint32_t meta_mode = INT_META ? kMetaInt : (meta_mode_arg == kMetaFp32 ? kMetaFp32 : kMetaBf16);
     // The tensor may be cut into equal slices, each packed into a record of its own (records `record_stride` bytes
     // apart); slice_lanes is a multiple of 64 then, so a wave's tile lies in one slice.  One slice: slice_lanes = n_lanes.
     constexpr int EPL = kEplStream;
@@ -1153,18 +1156,22 @@ static inline int launch_status() { return hipGetLastError() == hipSuccess ? FCV
 
 static inline unsigned grid_lanes(uint32_t n_lanes) { return (unsigned)((n_lanes + kBlock - 1) / kBlock); }
 
-// Number of blocks of a persistent launch: enough to fill the chip, at most one wave per tile.
+// Number of blocks of a persistent launch.  A compute unit holds 8 blocks of the quantize kernel (64 registers per
+// lane, 20 KiB of LDS per block).  A tensor of at most that many tiles gets one wave per tile, all resident at once;
+// a larger one gets 4 blocks per compute unit, each wave walking several tiles with the next loads in flight.
+// FCV2_BLOCKS_PER_CU overrides the choice (for experiments).
 static unsigned persistent_grid(uint32_t n_tiles) {
-    static int blocks = 0;
-    if (blocks == 0) {
-        int dev = 0, cus = 256;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
-        int per_cu = 4;
-        if (const char* e = getenv("FCV2_BLOCKS_PER_CU")) per_cu = atoi(e) > 0 ? atoi(e) : per_cu;
-        blocks = cus * per_cu;
+    static int cus = 0, forced = 0;
+    if (cus == 0) {
+        int dev = 0, n = 256;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 256;
+        if (const char* e = getenv("FCV2_BLOCKS_PER_CU")) forced = atoi(e) > 0 ? atoi(e) : 0;
+        cus = n > 0 ? n : 256;
     }
     const unsigned need = (n_tiles + kWaves - 1) / kWaves;
-    return need < (unsigned)blocks ? need : (unsigned)blocks;
+    const unsigned per_cu = forced ? (unsigned)forced : (need <= 8u * (unsigned)cus ? 8u : 4u);
+    const unsigned blocks = per_cu * (unsigned)cus;
+    return need < blocks ? need : blocks;
 }
 
 template <int BITS, int G, bool SR> struct LaunchQuantize {
@@ -1173,8 +1180,12 @@ template <int BITS, int G, bool SR> struct LaunchQuantize {
         constexpr int EPL = kEplStream;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
         const uint32_t n_tiles = (n_lanes + 63) / 64;
-        hipLaunchKernelGGL((k_quantize_pack_t<BITS, G / EPL, SR>), dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
-                           (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_mode, n_lanes / n_slices, record_stride);
+        if (meta_mode == kMetaInt)
+            hipLaunchKernelGGL((k_quantize_pack_t<BITS, G / EPL, SR, true>), dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
+                               (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_mode, n_lanes / n_slices, record_stride);
+        else
+            hipLaunchKernelGGL((k_quantize_pack_t<BITS, G / EPL, SR, false>), dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
+                               (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_mode, n_lanes / n_slices, record_stride);
         return launch_status();
     }
 };
