@@ -766,9 +766,14 @@ template <int EPL> __device__ __forceinline__ void patch_spikes(const GroupMeta&
 }
 
 template <int BITS, int EPL, int LPG, bool SR>
-__global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
+// Peers are taken two at a time (both peers' loads issued before either is decoded).  Every peer in flight costs
+// about 15 registers; with two the kernel needs 65 to 74 and six or seven waves fit a SIMD, which measured faster
+// than four peers in flight at four or five waves, and faster than one peer at eight.
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6)))
+void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
                                                            uint8_t* __restrict__ out, Rec rec_out, float* __restrict__ sum_out,
                                                            uint32_t meta_mode_in, uint32_t meta_mode_out) {
+    constexpr int CH = 2;  // peers in flight
     constexpr int ROW = EPL / 4 + 1;  // uint4 per private patch row, one of padding: conflict-free 16-byte accesses
     __shared__ uint4 lds[kBlock * ROW];
     __shared__ float tabs[kScaleTables];
@@ -794,18 +799,18 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant(PeerPtrs peers, int n
             for (int j = 0; j < EPL; ++j) acc[j] = __fadd_rn(acc[j], v[j]);
         };
         int p = 0;
-        // four peers at a time: all loads first, so their latencies overlap
-        for (; p + 4 <= n_peers; p += 4) {
-            RawPlanes<EPL> r[4];
-            uint32_t mraw[4];
+        // CH peers at a time: all loads first, so their latencies overlap
+        for (; p + CH <= n_peers; p += CH) {
+            RawPlanes<EPL> r[CH];
+            uint32_t mraw[CH];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < CH; ++i) {
                 const BufferSrc src = buffer_src(peers.base[p + i], rec_in.total);
                 r[i] = load_planes<BITS, EPL>(src, rec_in, L);
                 mraw[i] = ld32(src, mo.at);
             }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) add_peer(r[i], mraw[i]);
+            for (int i = 0; i < CH; ++i) add_peer(r[i], mraw[i]);
         }
         for (; p < n_peers; ++p) {
             const BufferSrc src = buffer_src(peers.base[p], rec_in.total);
