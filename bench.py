@@ -25,8 +25,8 @@ HBM_PEAK_GBS = 8000.0
 LLC_BYTES = 256 << 20
 ALU_PEAK_TLOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # 39.3 T lane-operations/s: VALU issue without packed fp32
 # Measured with rocprofv3 counters at the headline shape (profiles/headline_step_b3_g128_n8.md); per launch.
-TRAFFIC_BYTES = {"quantize_pack": 41.38e6, "reduce_requant": 74.90e6, "unpack_dequant": 41.21e6}
-VALU_OPS_PER_ELEMENT = {"quantize_pack": 18.2, "reduce_requant": 67.2, "unpack_dequant": 6.6}
+TRAFFIC_BYTES = {"quantize_pack": 41.29e6, "reduce_requant": 74.87e6, "unpack_dequant": 41.21e6}
+VALU_OPS_PER_ELEMENT = {"quantize_pack": 17.5, "reduce_requant": 66.4, "unpack_dequant": 6.6}
 
 
 def packed_bytes(n, bits, group, spike=True, int_meta=False):
@@ -158,7 +158,7 @@ def main():
                        gbs=round(ab[k] / (kern_ms[k] * 1e-3) / 1e9, 1),
                        frac_of_hbm_peak=round(ab[k] / (kern_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)) for k in ab}
     dom = "reduce_requant"
-    roofline = dict(bound="hbm", kernel=f"k_reduce_requant<3,16,8,true> ({dom}, N={n_peers})",
+    roofline = dict(bound="hbm", kernel=f"k_reduce_requant<3, 16, 8, true> ({dom}, N={n_peers})",
                     achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(kernels[dom]["gbs"] / HBM_PEAK_GBS, 4), traffic=TRAFFIC_BYTES[dom],
                     traffic_source="profiles/headline_step_b3_g128_n8.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scaled by a copy of known size)")
