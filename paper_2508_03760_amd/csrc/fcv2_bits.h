@@ -254,4 +254,65 @@ template <int BITS> FCV2_HD void codes_pairs(uint32_t p8lo, uint32_t p8hi, uint3
 #undef FCV2_SHIFTED
 }
 
+// ---- 16 elements of a lane -> 8 registers of (element | element) 16-bit halves, for 2, 3 and 4 bits --------------
+// As above, but the fields are only masked, never moved to bit 0: each half ends up holding code << pos with
+// zeros around it, and the consumer folds 2^-pos into the scale it multiplies the half with (a half read as an
+// fp16 denormal is an exact integer multiple of 2^-24 at any position below bit 10).  PairMap says which element
+// sits where.  p2 = 32 bits (elements 0..15), p1 = 16 bits, p4a/p4b = elements 0..7 / 8..15.
+template <int BITS> struct PairMap;
+template <> struct PairMap<2> {  // 2-bit fields at offset 2e: direct for e = 0..4 (with e + 8), rotated by 10 for 5..7
+    static constexpr int n_pos = 5;
+    static constexpr int lo(int k) { return k; }
+    static constexpr int hi(int k) { return k + 8; }
+    static constexpr int pos(int k) { return k < 5 ? 2 * k : 2 * (k - 5); }
+};
+template <> struct PairMap<3> {  // 2-bit field at offset o with the extra bit below it: o = 2, 4, 6, 8
+    static constexpr int n_pos = 4;
+    static constexpr int lo(int k) { return k + 1; }
+    static constexpr int hi(int k) { return (k + 9) & 15; }
+    static constexpr int pos(int k) { return 2 * (k & 3) + 1; }
+};
+template <> struct PairMap<4> {  // nibbles at offset 0 and 4 of each half, directly and after a rotation by 8
+    static constexpr int n_pos = 2;
+    static constexpr int lo(int k) { return (k & 3) + 8 * (k >> 2); }
+    static constexpr int hi(int k) { return lo(k) + 4; }
+    static constexpr int pos(int k) { return 4 * (k & 1); }
+};
+
+FCV2_HD uint32_t rotr32(uint32_t x, int r) { return (x >> r) | (x << (32 - r)); }
+
+template <int BITS> FCV2_HD void codes_pairs16(uint32_t p4a, uint32_t p4b, uint32_t p2, uint32_t p1, uint32_t (&Q)[8]) {
+    if (BITS == 2) {
+        const uint32_t B = rotr32(p2, 10);  // element 5 at bit 0, 13 at bit 16
+#pragma unroll
+        for (int k = 0; k < 5; ++k) Q[k] = p2 & (0x00030003u << (2 * k));
+#pragma unroll
+        for (int k = 0; k < 3; ++k) Q[5 + k] = B & (0x00030003u << (2 * k));
+    } else if (BITS == 3) {
+        // extra bits spread to every second position: bit e -> 2e (and a copy at 2e + 1 that the masks drop)
+        uint32_t x = ((p1 << 8) | p1) & 0x00FF00FFu;
+        x = ((x << 4) | x) & 0x0F0F0F0Fu;
+        x = ((x << 2) | x) & 0x33333333u;
+        x = (x << 1) | x;
+        const uint32_t SA = x >> 1, SB = rotr32(x, 9);  // bit of element e at 2e - 1, resp. at 2e - 9
+        const uint32_t B = rotr32(p2, 8);               // field of element 5 at bit 2, of 13 at bit 18, of 0 at bit 24
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int o = 2 * k + 2;
+            Q[k] = (p2 & (0x00030003u << o)) | (SA & (0x00010001u << (o - 1)));
+            Q[4 + k] = (B & (0x00030003u << o)) | (SB & (0x00010001u << (o - 1)));
+        }
+    } else {
+        const uint32_t Ba = rotr32(p4a, 8), Bb = rotr32(p4b, 8);
+        Q[0] = p4a & 0x000F000Fu;
+        Q[1] = p4a & 0x00F000F0u;
+        Q[2] = Ba & 0x000F000Fu;
+        Q[3] = Ba & 0x00F000F0u;
+        Q[4] = p4b & 0x000F000Fu;
+        Q[5] = p4b & 0x00F000F0u;
+        Q[6] = Bb & 0x000F000Fu;
+        Q[7] = Bb & 0x00F000F0u;
+    }
+}
+
 }  // namespace fcv2

@@ -39,6 +39,22 @@ template <int BITS> static void pairs_of_planes(uint32_t p8lo, uint32_t p8hi, ui
     }
 }
 
+// 16 codes from the masked-in-place pair registers: every half must be code << pos with nothing else set.
+template <int BITS> static int pairs16_of_planes(uint32_t p4a, uint32_t p4b, uint32_t p2, uint32_t p1, uint8_t* codes) {
+    uint32_t Q[8];
+    codes_pairs16<BITS>(p4a, p4b, p2, p1, Q);
+    using M = PairMap<BITS>;
+    for (int e = 0; e < 16; ++e) codes[e] = 0xEE;
+    for (int k = 0; k < 8; ++k) {
+        const uint32_t l = Q[k] & 0xFFFFu, h = Q[k] >> 16;
+        const uint32_t field = ((1u << BITS) - 1u) << M::pos(k);
+        if ((l & ~field) || (h & ~field) || M::pos(k) + BITS > 10) return -2;
+        codes[M::lo(k)] = (uint8_t)(l >> M::pos(k));
+        codes[M::hi(k)] = (uint8_t)(h >> M::pos(k));
+    }
+    return 0;
+}
+
 template <int QMAX> static uint64_t div_mismatches(uint32_t first_bits, uint32_t count) {
     uint64_t bad = 0;
     for (uint32_t i = 0; i < count; ++i) {
@@ -76,6 +92,15 @@ int hc_pairs_of_planes(int bits, uint32_t p8lo, uint32_t p8hi, uint32_t p4, uint
 #define C(B) case B: pairs_of_planes<B>(p8lo, p8hi, p4, p2, p1, codes); return 0;
         C(2) C(3) C(4) C(5) C(6) C(7) C(8)
 #undef C
+    }
+    return -1;
+}
+
+int hc_pairs16_of_planes(int bits, uint32_t p4a, uint32_t p4b, uint32_t p2, uint32_t p1, uint8_t* codes) {
+    switch (bits) {
+        case 2: return pairs16_of_planes<2>(p4a, p4b, p2, p1, codes);
+        case 3: return pairs16_of_planes<3>(p4a, p4b, p2, p1, codes);
+        case 4: return pairs16_of_planes<4>(p4a, p4b, p2, p1, codes);
     }
     return -1;
 }

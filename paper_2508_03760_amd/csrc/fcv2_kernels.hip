@@ -719,6 +719,24 @@ template <int BITS, int EPL>
 __device__ __forceinline__ void dequant_mix(const RawPlanes<EPL>& r, float s, float lo, float (&v)[EPL]) {
     typedef _Float16 half2v __attribute__((ext_vector_type(2)));
     using P = Planes<BITS>;
+    if constexpr (EPL == 16 && BITS <= 4) {
+        if (s < 0x1p+100f) {
+            // Narrow codes are only masked in place (code << pos in each half); 2^-pos goes into the multiplier.
+            using M = PairMap<BITS>;
+            uint32_t Q[8];
+            codes_pairs16<BITS>(P::w4 ? r.p4[0] : 0u, P::w4 ? r.p4[EPL / 8 - 1] : 0u, P::w2 ? r.p2[0] : 0u, P::w1 ? r.p1 : 0u, Q);
+            float mult[9];
+#pragma unroll
+            for (int q = 0; q < 9; ++q) mult[q] = s * __builtin_ldexpf(1.0f, 24 - q);  // only the positions in use survive
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+                const half2v h = __builtin_bit_cast(half2v, Q[k]);
+                v[M::lo(k)] = __builtin_fmaf((float)h.x, mult[M::pos(k)], lo);
+                v[M::hi(k)] = __builtin_fmaf((float)h.y, mult[M::pos(k)], lo);
+            }
+            return;
+        }
+    }
     if (s < 0x1p+100f) {  // always, unless the data spans more than 2^100: then 2^24 * scale could overflow
         const float s24 = s * 0x1p+24f;
 #pragma unroll

@@ -141,6 +141,29 @@ def test_plane_packing_sequences_match_oracle(hc, bits):
         assert np.array_equal(back, codes), (bits, codes, back)
 
 
+@pytest.mark.parametrize("bits", [2, 3, 4])
+def test_sixteen_element_pair_decoding(hc, bits):
+    """The reduce kernel's decoder for 16 elements per lane: planes packed by the oracle come back as the same codes,
+    every 16-bit half holds code << pos and nothing else."""
+    rng = np.random.default_rng(40 + bits)
+    cases = [rng.integers(0, 2 ** bits, 16).astype(np.uint8) for _ in range(400)]
+    cases += [np.full(16, 2 ** bits - 1, np.uint8), np.zeros(16, np.uint8)]
+    cases += [np.eye(16, dtype=np.uint8)[i] * (2 ** bits - 1) for i in range(16)]
+    cases += [np.eye(16, dtype=np.uint8)[i] for i in range(16)]
+    for codes in cases:
+        L = O.get_layout(16, bits, 16, 0, align=1)
+        packed = O.split_pack(codes, bits, 16, 0, align=1)
+        plane = {}
+        for w, nbytes in ((4, 8), (2, 4), (1, 2)):
+            off = getattr(L, f"off_plane{w}")
+            plane[w] = 0 if off == O.ABSENT else int.from_bytes(packed[off:off + nbytes].tobytes(), "little")
+        back = np.zeros(16, np.uint8)
+        rc = hc.hc_pairs16_of_planes(bits, plane[4] & 0xFFFFFFFF, plane[4] >> 32, plane[2], plane[1],
+                                     back.ctypes.data_as(C.POINTER(C.c_uint8)))
+        assert rc == 0, (bits, codes)
+        assert np.array_equal(back, codes), (bits, codes, back)
+
+
 def test_bf16_helpers_match_oracle(hc):
     for u in range(0, 65536, 7):
         assert hc.hc_key_of_bf16(u) == O.key(u)
