@@ -157,6 +157,42 @@ def test_every_scale_value(bits):
     check_codec(x, bits, 32, SR | INT, f"scales sr int b{bits}")
 
 
+def test_maximum_tensor_size():
+    """2^31 elements, the largest tensor a call takes (4 GiB of bf16): the 16M-element payload repeated 128 times on the
+    GPU.  Groups are independent, so every 16M-element block of the packed record must equal the oracle's record of
+    the payload, section by section; the same for the decoded tensor.  Exercises the 32-bit offsets at their limit."""
+    bits, group, flags = 2, 128, SR
+    base = W.tensor(2, 0).reshape(-1)
+    reps = (1 << 31) // base.size
+    n = base.size * reps
+    Lb = O.get_layout(base.size, bits, group, flags)
+    want = O.quantize_pack(base, bits, group, flags)
+    x = to_dev_bf16(base).repeat(reps)
+    assert x.numel() == 1 << 31
+    got = fcv2.quantize_pack(x, bits, group, flags)
+    L = fcv2.get_layout(n, bits, group, flags)
+    assert L.total_bytes < 1 << 32
+    want_d = torch.from_numpy(want).to(DEV)
+    for name, off, size in sections(L, flags):
+        per = size // reps
+        boff = getattr(Lb, "off_" + name)
+        blocks = got[off:off + size].view(reps, per)
+        assert torch.equal(blocks, want_d[boff:boff + per].expand(reps, per)), f"max size: section {name}"
+    out = fcv2.unpack_dequant(got, n, bits, group, flags, torch.bfloat16)
+    want_out = torch.from_numpy(O.unpack_dequant(want, base.size, bits, group, flags, O.DT_BF16).view(np.int16)).to(DEV)
+    assert torch.equal(out.view(torch.int16).view(reps, base.size), want_out.expand(reps, base.size)), "max size: unpack_dequant"
+    del x, out
+    # the local reduce step at the same size: two peers, the second one the first record again
+    red = fcv2.reduce_requant([got, got], n, (bits, group, flags))
+    want_red = torch.from_numpy(O.reduce_requant([want, want], base.size, (bits, group, flags))).to(DEV)
+    for name, off, size in sections(L, flags):
+        per = size // reps
+        boff = getattr(Lb, "off_" + name)
+        assert torch.equal(red[off:off + size].view(reps, per), want_red[boff:boff + per].expand(reps, per)), f"max size reduce: {name}"
+    del got, red
+    torch.cuda.empty_cache()
+
+
 # ---- reduce_requant -----------------------------------------------------------------------------------------------
 
 def check_reduce(xs, bits, group, flags, what, flags_out=None, bits_out=None):

@@ -66,7 +66,7 @@ def test_get_layout_matches_oracle_and_rejects_bad_input(lib):
     from paper_2508_03760_amd import fcv2
     for bits in range(2, 9):
         for group in (32, 64, 128, 256):
-            for flags in (0, 1, 2, 3):
+            for flags in (0, 1, 2, 3, 4, 5):
                 for align in (16, 256):
                     for n in (group, 4096, 7168 * 4):
                         if n % group:
@@ -86,6 +86,8 @@ def test_get_layout_matches_oracle_and_rejects_bad_input(lib):
         fcv2.get_layout(4096, 4, 128, 8)
     with pytest.raises(fcv2.Fcv2Error):
         fcv2.get_layout(4096, 4, 128, 1, 48)
+    with pytest.raises(fcv2.Fcv2Error):
+        fcv2.get_layout(4096, 4, 128, 2 | 4)  # fp32 and integer metadata exclude each other
     assert fcv2.dispatch_workspace_bytes(8192, 8, 256) > 8192 * 8 * 4
 
 
@@ -97,6 +99,10 @@ def test_null_and_misaligned_arguments_are_refused_on_the_host(lib):
     assert lib.fcv2_quantize_pack(None, 4096, C.byref(fmt), vp(256), None) == -1
     assert lib.fcv2_quantize_pack(vp(256), 4096, C.byref(fmt), vp(264), None) == -3  # not 16-byte aligned
     assert lib.fcv2_quantize_pack(vp(256), 4000, C.byref(fmt), vp(512), None) == -1
+    assert lib.fcv2_quantize_pack(vp(256), (1 << 31) + 4096, C.byref(fmt), vp(512), None) == -2  # above the largest tensor
+    lib.fcv2_unpack_dequant.argtypes = [vp, C.c_uint64, C.POINTER(_Fmt), vp, C.c_int, vp]
+    assert lib.fcv2_unpack_dequant(vp(256), (1 << 31) + 4096, C.byref(fmt), vp(512), 0, None) == -2
+    assert lib.fcv2_unpack_dequant(vp(256), 4096, C.byref(fmt), vp(512), 7, None) == -1  # unknown output type
     lib.fcv2_reduce_requant.argtypes = [C.POINTER(vp), C.c_int, C.c_uint64, C.POINTER(_Fmt), C.POINTER(_Fmt), vp, vp, vp]
     peers = (vp * 2)(256, 512)
     assert lib.fcv2_reduce_requant(peers, 0, 4096, C.byref(fmt), C.byref(fmt), vp(1024), None, None) == -1
