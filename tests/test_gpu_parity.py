@@ -415,6 +415,35 @@ def test_dispatch_quant_degenerate_routing():
     assert int(offs.cpu().numpy().max()) == 0
 
 
+def test_dispatch_maximum_input_size():
+    """T x H = 2^31 elements (262,144 tokens of 8,192, one copy each): 1,024 seeded tokens repeated on the GPU.  The
+    routing is checked against its definition (stable sort by expert), every row against the oracle's record of its
+    token."""
+    bits, group, flags = 2, 128, SR
+    base_T, H, E, K = 1024, 8192, 64, 1
+    reps = (1 << 31) // (base_T * H)
+    T = base_T * reps
+    base = W.tensor(3, 4, rows=base_T, cols=H)
+    x = to_dev_bf16(base).view(base_T, H).repeat(reps, 1)
+    rng = np.random.default_rng(77)
+    ids = rng.integers(0, E, (T, K)).astype(np.int32)
+    ids[rng.integers(0, T, 1000), 0] = -1
+    send, offs, src = fcv2.dispatch_quant(x, torch.from_numpy(ids).to(DEV), E, bits, group, flags)
+    flat = ids.reshape(-1)
+    routed = np.nonzero(flat >= 0)[0]
+    order = routed[np.argsort(flat[routed], kind="stable")]
+    R = order.size
+    want_offs = np.concatenate([[0], np.cumsum(np.bincount(flat[routed], minlength=E))]).astype(np.int32)
+    assert np.array_equal(offs.cpu().numpy(), want_offs)
+    assert np.array_equal(src.cpu().numpy()[:R], order.astype(np.int32))
+    L = O.get_layout(H, bits, group, flags, 16)
+    rows_o = np.stack([O.quantize_pack(base[t], bits, group, flags, align=16) for t in range(base_T)])
+    rows_d = torch.from_numpy(rows_o).to(DEV)
+    tok = torch.from_numpy((order // K) % base_T).to(DEV)
+    for name, off, size in sections(L, flags):
+        assert torch.equal(send[:R, off:off + size], rows_d[tok][:, off:off + size]), f"max dispatch: section {name}"
+
+
 # ---- the five workloads at full size, in the launch configuration the benchmark times ----------------------------------
 
 def test_workload1_full():
