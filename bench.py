@@ -26,7 +26,7 @@ LLC_BYTES = 256 << 20
 ALU_PEAK_TLOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # 39.3 T lane-operations/s: VALU issue without packed fp32
 # Measured with rocprofv3 counters at the headline shape (profiles/headline_step_b3_g128_n8.md); per launch.
 TRAFFIC_BYTES = {"quantize_pack": 41.29e6, "reduce_requant": 74.87e6, "unpack_dequant": 41.21e6}
-VALU_OPS_PER_ELEMENT = {"quantize_pack": 17.5, "reduce_requant": 66.4, "unpack_dequant": 6.6}
+VALU_OPS_PER_ELEMENT = {"quantize_pack": 17.5, "reduce_requant": 62.8, "unpack_dequant": 6.6}
 
 
 def packed_bytes(n, bits, group, spike=True, int_meta=False):
