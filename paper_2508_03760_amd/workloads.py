@@ -88,7 +88,7 @@ def activations(seed: int, rows: int, cols: int, col_block: int = 128, channel_s
     """N(0,1) times a lognormal(0, 0.5) scale per block of `col_block` columns (shared by all rows);
     0.1 % of the elements multiplied by +-50.  Shape [rows, cols], bf16 bits.  (Workloads 1, 2, 3.)"""
     n = rows * cols
-    c = column_scales(seed, cols // col_block) if channel_scale else None
+    c = column_scales(seed, -(-cols // col_block)) if channel_scale else None  # a last, shorter block gets a scale too
 
     def fn(s, cnt):
         z, _, _ = _normal_pair(seed, s, cnt)
@@ -123,9 +123,8 @@ def decode_spiky(seed: int, rows: int, cols: int, group: int = 128, spike: float
     u = uniform(seed ^ 0x51DE, 0, ng, 0)
     v = uniform(seed ^ 0x51DE, 0, ng, 1)
     pos = np.minimum((u * group).astype(np.int64), group - 1)
-    z = z.reshape(ng, group)
-    z[np.arange(ng), pos] = np.where(v <= 0.5, -spike, spike)
-    return f32_to_bf16_bits(z.reshape(-1).astype(np.float32)).reshape(rows, cols)
+    z[np.arange(ng) * group + pos] = np.where(v <= 0.5, -spike, spike)  # elements past the last whole group stay plain
+    return f32_to_bf16_bits(z.astype(np.float32)).reshape(rows, cols)
 
 
 def topk_routing(seed: int, tokens: int, experts: int, k: int, zipf_a: float = 1.1) -> np.ndarray:

@@ -157,6 +157,24 @@ def test_every_scale_value(bits):
     check_codec(x, bits, 32, SR | INT, f"scales sr int b{bits}")
 
 
+def test_random_shapes_and_formats():
+    """Forty seeded draws of (length, bits, group, flags): lengths are any whole number of groups (multiples of 8
+    elements), so tiles end anywhere; codec, reduce over a random number of peers, and the sliced calls where the
+    length allows them."""
+    rng = np.random.default_rng(2508)
+    for case in range(40):
+        bits = int(rng.integers(2, 9))
+        group = int(rng.choice([32, 64, 128, 256]))
+        flags = int(rng.choice([0, SR, SR | F32, SR | INT, INT, F32]))
+        n = group * int(rng.integers(1, 200))
+        kind = int(rng.integers(1, 6))
+        x = W.tensor(kind, case % 8, rows=1, cols=n).reshape(-1)
+        check_codec(x, bits, group, flags, f"random case {case}: n={n} b{bits} g{group} f{flags}")
+        n_peers = int(rng.integers(1, 7))
+        xs = [W.tensor(kind, (case + p) % 8, rows=1, cols=n).reshape(-1) for p in range(n_peers)]
+        check_reduce(xs, bits, group, flags, f"random case {case}: reduce N={n_peers} n={n} b{bits} g{group} f{flags}")
+
+
 def test_maximum_tensor_size():
     """2^31 elements, the largest tensor a call takes (4 GiB of bf16): the 16M-element payload repeated 128 times on the
     GPU.  Groups are independent, so every 16M-element block of the packed record must equal the oracle's record of
