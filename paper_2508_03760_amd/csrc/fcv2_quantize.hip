@@ -1,0 +1,103 @@
+// fcv2_quantize.hip -- fcv2_quantize_pack(_slices): the sender-side kernel and its launch.
+#include "fcv2_host.h"
+
+namespace fcv2 {
+
+// Sender: persistent waves walk over the tiles; the next tile's loads are in flight while the current one is
+// quantized, so memory and arithmetic overlap inside every wave.
+template <int BITS, int LPG, bool SR, bool INT_META>
+__global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restrict__ x, uint32_t n_lanes, uint8_t* __restrict__ out,
+                                                            Rec rec, uint32_t meta_mode_arg, uint32_t slice_lanes,
+                                                            uint64_t record_stride) {
+    // The integer metadata path is a compile-time variant here: its tables and extra live values would otherwise
+    // cost the float formats a third of their registers (and with them two waves per SIMD).
+    const uint32_t meta_mode = INT_META ? kMetaInt : (meta_mode_arg == kMetaFp32 ? kMetaFp32 : kMetaBf16);
+    // The tensor may be cut into equal slices, each packed into a record of its own (records `record_stride` bytes
+    // apart); slice_lanes is a multiple of 64 then, so a wave's tile lies in one slice.  One slice: slice_lanes = n_lanes.
+    constexpr int EPL = kEplStream;
+    __shared__ uint4 lds[kWaves][64 * kRowU4];
+    __shared__ float tabs[kScaleTables];
+    if (meta_mode == kMetaInt) fill_scale_tables(tabs);
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));  // uniform: tiles are per wave
+    const uint32_t lig = lane & (LPG - 1);
+    const uint32_t n_tiles = (n_lanes + 63) / 64;
+    const uint32_t stride = gridDim.x * kWaves;
+    uint32_t tile = blockIdx.x * kWaves + wave;
+    if (tile >= n_tiles) return;
+    const uint32_t n_pieces = n_lanes * 4;
+    auto process = [&](const TileIn& t, uint32_t tl) {
+        uint32_t w[16];
+        tile_transpose(t, lds[wave], lane, w);
+        const uint32_t slice = (tl * 64) / slice_lanes;  // uniform
+        const uint32_t L = tl * 64 + lane;
+        if (L < n_lanes) {  // groups never straddle the end: whole groups are in or out together
+            uint32_t c[EPL / 4];
+            GroupMeta m;
+            quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode, tabs, &lds[wave][lane * kRowU4], c, m);
+            uint8_t* o = out + slice * record_stride;
+            const uint32_t Lr = L - slice * slice_lanes;  // lane inside the record
+            store_planes<BITS, EPL>(o, rec, Lr, c);
+            if (lig == 0) store_meta<SR>(o, rec, Lr / LPG, m, meta_mode);
+        }
+    };
+    // Two tiles are kept in flight per wave (two register sets, ping-pong, so loaded data is never moved); the
+    // refill of a set is issued right after the tile that used it has been stored.  Loads are unconditional
+    // (past the end they re-read the last tile): conditional ones would force full waits.
+    const uint32_t last = n_tiles - 1;
+    TileIn a = tile_load(x, (uint64_t)tile * 256, lane, n_pieces - tile * 256);
+    uint32_t t1 = min(tile + stride, last);
+    TileIn b = tile_load(x, (uint64_t)t1 * 256, lane, n_pieces - t1 * 256);
+    while (true) {
+        process(a, tile);
+        uint32_t t2 = min(tile + 2 * stride, last);
+        a = tile_load(x, (uint64_t)t2 * 256, lane, n_pieces - t2 * 256);
+        tile += stride;
+        if (tile >= n_tiles) break;
+        process(b, tile);
+        t2 = min(tile + 2 * stride, last);
+        b = tile_load(x, (uint64_t)t2 * 256, lane, n_pieces - t2 * 256);
+        tile += stride;
+        if (tile >= n_tiles) break;
+    }
+}
+
+// Number of blocks of a persistent launch.  A compute unit holds 8 blocks of the quantize kernel (64 registers per
+// lane, 20 KiB of LDS per block).  A tensor of at most that many tiles gets one wave per tile, all resident at once;
+// a larger one gets 4 blocks per compute unit, each wave walking several tiles with the next loads in flight.
+// FCV2_BLOCKS_PER_CU overrides the choice (for experiments).
+static unsigned persistent_grid(uint32_t n_tiles) {
+    static int cus = 0, forced = 0;
+    if (cus == 0) {
+        int dev = 0, n = 256;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 256;
+        if (const char* e = getenv("FCV2_BLOCKS_PER_CU")) forced = atoi(e) > 0 ? atoi(e) : 0;
+        cus = n > 0 ? n : 256;
+    }
+    const unsigned need = (n_tiles + kWaves - 1) / kWaves;
+    const unsigned per_cu = forced ? (unsigned)forced : (need <= 8u * (unsigned)cus ? 8u : 4u);
+    const unsigned blocks = per_cu * (unsigned)cus;
+    return need < blocks ? need : blocks;
+}
+
+template <int BITS, int G, bool SR> struct LaunchQuantize {
+    static int run(const void* x, uint64_t n, void* out, const Rec& rec, uint32_t meta_mode, uint32_t n_slices,
+                   uint64_t record_stride, hipStream_t st) {
+        constexpr int EPL = kEplStream;
+        const uint32_t n_lanes = (uint32_t)(n / EPL);
+        const uint32_t n_tiles = (n_lanes + 63) / 64;
+        if (meta_mode == kMetaInt)
+            hipLaunchKernelGGL((k_quantize_pack_t<BITS, G / EPL, SR, true>), dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
+                               (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_mode, n_lanes / n_slices, record_stride);
+        else
+            hipLaunchKernelGGL((k_quantize_pack_t<BITS, G / EPL, SR, false>), dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
+                               (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_mode, n_lanes / n_slices, record_stride);
+        return launch_status();
+    }
+};
+int launch_quantize(const fcv2_fmt_t* fmt, const void* x, uint64_t n, void* out, const Rec& rec, uint32_t n_slices,
+                    uint64_t record_stride, hipStream_t st) {
+    return by_format<LaunchQuantize>(fmt, x, n, out, rec, meta_mode_of(fmt), n_slices, record_stride, st);
+}
+
+}  // namespace fcv2
