@@ -162,7 +162,7 @@ def main():
                     achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(kernels[dom]["gbs"] / HBM_PEAK_GBS, 4), traffic=TRAFFIC_BYTES[dom],
                     traffic_source="profiles/headline_step_b3_g128_n8.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scaled by a copy of known size)")
-    # the same kernel against the bound that actually limits it at 3 bits: VALU issue (see DESIGN.md)
+    # the same kernel against the bound that actually limits it at 3 bits: VALU issue
     # executed = VALU instructions per output element as counted by rocprofv3; algorithmic = what the definition itself
     # needs per output element at N peers: per peer-element extract + FMA + add, per output element bf16 rounding (1/2),
     # order key, two running top-2 selections (2 x 2), subtract, multiply, convert, pack

@@ -23,7 +23,9 @@
  * reassembly; reduction against float64 sums and special cases; a float64 textbook RTN quantizer
  * when spike reserving is off.  Parity unpinned by the paper (pinned only by this build's own
  * format statement and by round trips): which bits of a code go to which plane, the bit order
- * inside plane bytes, and the code value stored at spike positions.
+ * inside plane bytes, and the code value stored at spike positions.  The one-byte "zero" of Table 4's second row
+ * is read as the textbook integer zero-point over a range widened to contain 0 (the table gives only its size):
+ * the reading is unpinned by the paper, its arithmetic is pinned against the textbook affine quantizer.
  */
 #ifndef FCV2_ORACLE_H
 #define FCV2_ORACLE_H
