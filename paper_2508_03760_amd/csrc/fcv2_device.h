@@ -4,8 +4,8 @@
 // LPG = G/EPL neighbouring lanes, so group reductions are DPP butterflies inside a 16-lane row.  The kernels
 // that stream a tensor once (quantize_pack, unpack_dequant, dispatch_quant) use EPL = 32 (64 bytes of bf16 per
 // lane, LPG = 1..8): per-lane overheads are paid once per 32 elements, and a wave's tile of 2048 elements is moved
-// with coalesced 16-byte accesses and transposed through LDS.  reduce_requant uses EPL = 16 (8 for groups of 32, so
-// that a group still spans a quad): its accumulators and the values of one peer live in registers, and the spike
+// with coalesced 16-byte accesses and transposed through LDS.  reduce_requant uses EPL = 16 (a group
+// is 2 to 16 lanes): its accumulators and the values of one peer live in registers, and the spike
 // positions of every peer are patched through LDS.  The paper's own block shape (512 threads x 8 values,
 // Section 4.1) was made for other hardware and is not followed.
 //
@@ -477,39 +477,72 @@ template <int BITS, int EPL> __device__ __forceinline__ void unit_codes(const Ra
     }
 }
 
-// --- metadata fetched by quads (reduce_requant) ---------------------------------------------------------------
-// Lane & 3 of every quad fetches one of the group's four metadata items (scale, zero, spike values, spike indices)
-// as the aligned dword that holds it; quad broadcasts hand the four to every lane.  Address and byte selector of
-// "its" item are computed once per lane and reused for every peer.
+// --- metadata fetched cooperatively (reduce_requant) --------------------------------------------------------------
+// The lanes of a group share the fetch of its four metadata items (scale, zero, spike values, spike indices), each
+// read as the aligned dword that holds it and moved into place by one byte permute.  Groups of four or more lanes:
+// lane & 3 of every quad fetches one item, quad broadcasts hand the four to every lane.  Groups of two lanes: the even
+// lane fetches scale and spike values, the odd lane zero and spike indices, pair broadcasts hand them over.  Addresses
+// and selectors are computed once per lane and reused for every peer.
 struct MetaOffsets {
-    uint32_t at;   // aligned dword that holds the item
-    uint32_t sel;  // byte selector (v_perm_b32) that moves the item to where its consumer wants it
+    uint32_t at, sel;    // aligned dword of the (first) item and its byte selector (v_perm_b32)
+    uint32_t at2, sel2;  // second item, two-lane groups with spike reserving only
 };
 
-template <int LPG, bool SR> __device__ __forceinline__ MetaOffsets meta_offsets(const Rec& r, uint32_t L, uint32_t mode) {
-    const uint32_t g = L / LPG, item = L & 3u;
+// kind: 0 scale, 1 zero, 2 spike values, 3 spike indices.  Selector bytes: 4 + k = byte k of the dword, 0x0C = zero.
+__device__ __forceinline__ void meta_item(const Rec& r, uint32_t g, uint32_t mode, uint32_t kind, uint32_t& at_dword, uint32_t& sel) {
     const uint32_t msz = (mode == kMetaFp32) ? 4u : (mode == kMetaInt) ? 1u : 2u;
-    uint32_t at = r.scale + msz * g;               // item 0, and every item when there are no spikes
-    if (item == 1u) at = r.zero + msz * g;
-    if (SR && item == 2u) at = r.spike_val + 4u * g;
-    if (SR && item == 3u) at = r.spike_idx + 2u * g;
-    MetaOffsets o;
-    o.at = at & ~3u;
-    // Selector bytes: 4 + k = byte k of the loaded dword, 0x0C = zero.
+    uint32_t at = r.scale + msz * g;
+    if (kind == 1u) at = r.zero + msz * g;
+    if (kind == 2u) at = r.spike_val + 4u * g;
+    if (kind == 3u) at = r.spike_idx + 2u * g;
     const uint32_t b0 = 4u + (at & 3u), b1 = b0 + 1u;
-    uint32_t sel = 0x07060504u;                                                      // fp32 items, spike values: as loaded
-    if (mode == kMetaBf16) sel = 0x00000C0Cu | (b0 << 16) | (b1 << 24);              // bf16 -> the upper half: fp32 bits
-    if (mode == kMetaInt) sel = 0x0C0C0C00u | b0;                                    // one byte -> the low byte
-    if (SR && item == 2u) sel = 0x07060504u;
-    if (SR && item == 3u) sel = 0x0C0C0000u | (b1 << 8) | b0;                        // two index bytes -> the low half
-    o.sel = sel;
+    uint32_t s = 0x07060504u;                                                 // fp32 items, spike values: as loaded
+    if (mode == kMetaBf16) s = 0x00000C0Cu | (b0 << 16) | (b1 << 24);         // bf16 -> the upper half: fp32 bits
+    if (mode == kMetaInt) s = 0x0C0C0C00u | b0;                               // one byte -> the low byte
+    if (kind == 2u) s = 0x07060504u;
+    if (kind == 3u) s = 0x0C0C0000u | (b1 << 8) | b0;                         // two index bytes -> the low half
+    at_dword = at & ~3u;
+    sel = s;
+}
+
+template <int LPG, bool SR> __device__ __forceinline__ MetaOffsets meta_offsets(const Rec& r, uint32_t L, uint32_t mode) {
+    const uint32_t g = L / LPG;
+    MetaOffsets o;
+    if (LPG >= 4) {
+        const uint32_t item = L & 3u;
+        meta_item(r, g, mode, SR ? item : (item & 1u), o.at, o.sel);  // without spikes lanes 2, 3 repeat 0, 1
+        o.at2 = o.at;
+        o.sel2 = o.sel;
+    } else {
+        const uint32_t odd = L & 1u;
+        meta_item(r, g, mode, odd, o.at, o.sel);
+        meta_item(r, g, mode, SR ? 2u + odd : odd, o.at2, o.sel2);
+    }
     return o;
 }
 
-template <bool SR, bool INT_META> __device__ __forceinline__ GroupMeta spread_meta(uint32_t raw, const MetaOffsets& o, const float* tabs) {
+// Value held by the even (ODD = 0) or odd lane of this lane's pair.
+template <int ODD> __device__ __forceinline__ uint32_t pair_bcast(uint32_t v) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, ODD ? 0xF5 : 0xA0, 0xF, 0xF, true);  // quad_perm [1,1,3,3] / [0,0,2,2]
+}
+
+template <int LPG, bool SR, bool INT_META>
+__device__ __forceinline__ GroupMeta spread_meta(uint32_t raw, uint32_t raw2, const MetaOffsets& o, const float* tabs) {
     const uint32_t val = __builtin_amdgcn_perm(raw, 0u, o.sel);
     GroupMeta m;
-    const uint32_t sb = quad_bcast<0>(val), zb = quad_bcast<1>(val);
+    uint32_t sb, zb;
+    if (LPG >= 4) {
+        sb = quad_bcast<0>(val);
+        zb = quad_bcast<1>(val);
+        m.sv = SR ? quad_bcast<2>(val) : 0u;
+        m.si = SR ? quad_bcast<3>(val) : 0u;
+    } else {
+        sb = pair_bcast<0>(val);
+        zb = pair_bcast<1>(val);
+        const uint32_t val2 = SR ? __builtin_amdgcn_perm(raw2, 0u, o.sel2) : 0u;
+        m.sv = SR ? pair_bcast<0>(val2) : 0u;
+        m.si = SR ? pair_bcast<1>(val2) : 0u;
+    }
     if (INT_META) {  // Eq. 1 inverted: 2^(scale_int / 10), offset = -(zero * scale)
         m.s = tabs[(sb ^ 0x80u) + 1u];  // entry k + 129 of the table of 2^(k/10)
         m.lo = -__fmul_rn((float)zb, m.s);
@@ -518,8 +551,6 @@ template <bool SR, bool INT_META> __device__ __forceinline__ GroupMeta spread_me
         m.lo = u2f(zb);
     }
     m.raw_s = m.raw_z = 0;
-    m.sv = SR ? quad_bcast<2>(val) : 0u;
-    m.si = SR ? quad_bcast<3>(val) : 0u;
     return m;
 }
 

@@ -3,7 +3,7 @@
 
 namespace fcv2 {
 
-// Local reduce step.  EPL = 16 elements per lane (8 for G = 32, so that a group still spans a whole quad).
+// Local reduce step.  EPL = 16 elements per lane (groups of 32 are two lanes, larger ones four to sixteen).
 //  - codes are unpacked into 16-bit halves and fed to v_fma_mix_f32 as fp16 denormals (q * 2^-24) against the
 //    scale pre-multiplied by 2^24: the product is the same real number q * scale, the FMA rounds once, so the
 //    result is bit-identical to fma(float(q), scale, lo) without a conversion instruction per element;
@@ -103,8 +103,8 @@ void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
     // The peer loop exists twice, once per kind of metadata decoding, chosen by one uniform branch outside it.
     auto sum_peers = [&](auto int_meta) {
         constexpr bool INT_META = decltype(int_meta)::value;
-        auto add_peer = [&](const RawPlanes<EPL>& r, uint32_t mraw) {
-            const GroupMeta m = spread_meta<SR, INT_META>(mraw, mo, tabs);
+        auto add_peer = [&](const RawPlanes<EPL>& r, uint32_t mraw, uint32_t mraw2) {
+            const GroupMeta m = spread_meta<LPG, SR, INT_META>(mraw, mraw2, mo, tabs);
             float v[EPL];
             dequant_mix<BITS, EPL>(r, m.s, m.lo, v);
             if (SR) patch_spikes<EPL>(m, lig, row, v);
@@ -115,21 +115,23 @@ void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
         // CH peers at a time: all loads first, so their latencies overlap
         for (; p + CH <= n_peers; p += CH) {
             RawPlanes<EPL> r[CH];
-            uint32_t mraw[CH];
+            uint32_t mraw[CH], mraw2[CH];
 #pragma unroll
             for (int i = 0; i < CH; ++i) {
                 const BufferSrc src = buffer_src(peers.base[p + i], rec_in.total);
                 r[i] = load_planes<BITS, EPL>(src, rec_in, L);
                 mraw[i] = ld32(src, mo.at);
+                mraw2[i] = (LPG < 4 && SR) ? ld32(src, mo.at2) : 0u;
             }
 #pragma unroll
-            for (int i = 0; i < CH; ++i) add_peer(r[i], mraw[i]);
+            for (int i = 0; i < CH; ++i) add_peer(r[i], mraw[i], mraw2[i]);
         }
         for (; p < n_peers; ++p) {
             const BufferSrc src = buffer_src(peers.base[p], rec_in.total);
             const RawPlanes<EPL> r = load_planes<BITS, EPL>(src, rec_in, L);
             const uint32_t mraw = ld32(src, mo.at);
-            add_peer(r, mraw);
+            const uint32_t mraw2 = (LPG < 4 && SR) ? ld32(src, mo.at2) : 0u;
+            add_peer(r, mraw, mraw2);
         }
     };
     if (meta_mode_in == kMetaInt)
@@ -174,7 +176,9 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
     for (int p = 0; p < n_peers; ++p) {
         const BufferSrc src = buffer_src(peers.base[p], rec_in.total);
         const uint32_t mraw = ld32(src, mo.at);
-        const GroupMeta m = (meta_mode_in == kMetaInt) ? spread_meta<SR, true>(mraw, mo, tabs) : spread_meta<SR, false>(mraw, mo, tabs);
+        const uint32_t mraw2 = (LPG < 4 && SR) ? ld32(src, mo.at2) : 0u;
+        const GroupMeta m = (meta_mode_in == kMetaInt) ? spread_meta<LPG, SR, true>(mraw, mraw2, mo, tabs)
+                                                       : spread_meta<LPG, SR, false>(mraw, mraw2, mo, tabs);
         float v[EPL];
         switch (bits_in) {
 #define FCV2_CASE(B)                                                      \
@@ -215,7 +219,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
 template <int BITS, int G, bool SR> struct LaunchReduce {
     static int run(const PeerPtrs& peers, int n_peers, uint64_t n, const Rec& rec_in, void* out, const Rec& rec_out,
                    float* sum_out, uint32_t mf_in, uint32_t mf_out, hipStream_t st) {
-        constexpr int EPL = G >= 64 ? 16 : 8;  // 32 was measured: 180 VGPRs, two waves per SIMD, 15 % slower
+        constexpr int EPL = 16;  // 32 was measured: 180 VGPRs, two waves per SIMD, 15 % slower; 8 doubles the per-lane work
         const uint32_t n_lanes = (uint32_t)(n / EPL);
         hipLaunchKernelGGL((k_reduce_requant<BITS, EPL, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st, peers,
                            n_peers, n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
@@ -225,7 +229,7 @@ template <int BITS, int G, bool SR> struct LaunchReduce {
 template <int BITS, int G, bool SR> struct LaunchReduceMixed {  // BITS = output width
     static int run(const PeerPtrs& peers, int n_peers, uint32_t bits_in, uint64_t n, const Rec& rec_in, void* out,
                    const Rec& rec_out, float* sum_out, uint32_t mf_in, uint32_t mf_out, hipStream_t st) {
-        constexpr int EPL = G >= 64 ? 16 : 8;
+        constexpr int EPL = 16;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
         hipLaunchKernelGGL((k_reduce_requant_mixed<BITS, EPL, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
                            peers, n_peers, bits_in, n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
