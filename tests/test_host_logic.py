@@ -238,3 +238,14 @@ def test_scale_int_ends_and_specials(hc):
             assert s[0] == np.float32(2.0 ** (want / 10.0))
     for kk in range(-128, 128):
         assert np.float32(hc.hc_scale_of_int(kk)) == np.float32(np.exp2(np.float64(kk) / 10.0))
+
+
+def test_bench_byte_formula_is_the_unpadded_record():
+    """The algorithmic bytes the benchmark divides by are the record's sections without alignment padding."""
+    import bench
+    for bits in range(2, 9):
+        for group in (32, 128, 256):
+            for spike in (False, True):
+                for int_meta in (False, True):
+                    flags = (O.F_SPIKE if spike else 0) | (O.F_META_INT if int_meta else 0)
+                    assert bench.packed_bytes(1 << 16, bits, group, spike, int_meta) == O.get_layout(1 << 16, bits, group, flags, align=1).total_bytes
