@@ -121,7 +121,8 @@ int fcv2_reduce_requant(const void* const* peers_dev, int n_peers, uint64_t n, c
  *   x_bf16_dev    [T, H] bf16, H % group == 0
  *   topk_ids_dev  [T, K] int32, expert id in [0, E) or -1 for a dropped slot
  *   send_buf_dev  R rows of row_bytes = fcv2_get_layout(H, fmt, FCV2_ROW_ALIGN).total_bytes, R = number of
- *                 ids != -1 (the caller may size it for T*K rows); row_bytes is a multiple of 16
+ *                 ids != -1 (the caller may size it for T*K rows); row_bytes is a multiple of 16; the padding
+ *                 between a row's sections is written as zero or left untouched
  *   expert_offsets_dev [E+1] int32 out: expert e owns rows [expert_offsets[e], expert_offsets[e+1])
  *   row_src_dev   [T*K] int32 out: entry r < R is t*K+k of the copy stored in row r; inside an expert rows are
  *                 in ascending t*K+k (a stable counting sort)
@@ -134,8 +135,8 @@ int fcv2_dispatch_quant(const void* x_bf16_dev, const int32_t* topk_ids_dev, uin
                         int32_t* row_src_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
 /* Diagnostic, not part of the codec: a plain streaming copy of `bytes` (a multiple of 16) from src_dev to
- * dst_dev, 16 bytes per lane.  The benchmark uses it to measure the practical HBM ceiling next to the codec
- * kernels and to calibrate memory-traffic counters against a transfer of known size. */
+ * dst_dev, 16 bytes per lane, stores with the non-temporal hint.  The benchmark uses it to measure the practical
+ * HBM ceiling next to the codec kernels and to calibrate memory-traffic counters against a transfer of known size. */
 int fcv2_stream_copy(const void* src_dev, void* dst_dev, uint64_t bytes, void* hip_stream);
 
 const char* fcv2_status_string(int status);

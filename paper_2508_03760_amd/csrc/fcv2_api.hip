@@ -7,7 +7,7 @@ namespace fcv2 {
 // Plain streaming copy (16 bytes per lane), used to measure the practical HBM ceiling next to the codec kernels.
 __global__ __launch_bounds__(kBlock) void k_stream_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, uint64_t n16) {
     const uint64_t i = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (i < n16) dst[i] = src[i];
+    if (i < n16) store_stream(&dst[i], src[i]);
 }
 
 static bool fmt_supported(const fcv2_fmt_t* f) {

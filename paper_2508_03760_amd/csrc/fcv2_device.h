@@ -60,6 +60,27 @@ __device__ __forceinline__ void fill_scale_tables(float* tabs) {
     __syncthreads();
 }
 
+// ---- streaming stores ---------------------------------------------------------------------------------------
+// Output that is written once and not read again by the same kernel goes out with the non-temporal hint wherever a
+// store instruction of the wave covers whole 128-byte lines.  Measured on the MI355X: a plain 16-byte-per-lane copy of
+// 256 MiB runs at 8.5 instead of 6.2 TB/s, unpack_dequant 16-25 % faster, the row copies of dispatch_quant 22 % faster.
+// Stores that touch a few bytes per line (metadata written by one lane in four, 16-byte pieces 32 bytes apart) are
+// slower with the hint and stay ordinary stores.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void store_stream(void* p, uint4 v) {
+    const u32x4 t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(p));
+}
+__device__ __forceinline__ void store_stream(void* p, uint2 v) {
+    const u32x2 t = {v.x, v.y};
+    __builtin_nontemporal_store(t, reinterpret_cast<u32x2*>(p));
+}
+__device__ __forceinline__ void store_stream(void* p, uint32_t v) { __builtin_nontemporal_store(v, reinterpret_cast<uint32_t*>(p)); }
+__device__ __forceinline__ void store_stream(void* p, uint16_t v) { __builtin_nontemporal_store(v, reinterpret_cast<uint16_t*>(p)); }
+__device__ __forceinline__ void store_stream(void* p, uint8_t v) { __builtin_nontemporal_store(v, reinterpret_cast<uint8_t*>(p)); }
+__device__ __forceinline__ void store_stream(void* p, float v) { __builtin_nontemporal_store(v, reinterpret_cast<float*>(p)); }
+
 // ---- cross-lane helpers -------------------------------------------------------------------------------------
 template <int CTRL> __device__ __forceinline__ uint32_t dpp(uint32_t v) {
     // old = identity of the unsigned minimum: the move folds into v_min_u32_dpp
@@ -291,6 +312,9 @@ __device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint
 }
 
 // Store the planes of this lane's EPL codes.  L = lane index inside the record (element index / EPL).
+// Plane stores: every store instruction of a wave covers consecutive bytes, and the record is on its way out of this
+// GPU, so they carry the non-temporal hint.
+#define ST(at, T, v) store_stream(at, (T)v)
 template <int BITS, int EPL> __device__ __forceinline__ void store_planes(uint8_t* base, const Rec& r, uint32_t L,
                                                                            const uint32_t (&c)[EPL / 4]) {
     using P = Planes<BITS>;
@@ -300,9 +324,9 @@ template <int BITS, int EPL> __device__ __forceinline__ void store_planes(uint8_
         for (int u = 0; u < U; u += 2) {
             uint8_t* at = base + (r.plane8 + (uint32_t)EPL * L + 8u * u);
             if (U >= 2)
-                *reinterpret_cast<uint4*>(at) = make_uint4(c[2 * u], c[2 * u + 1], c[2 * u + 2], c[2 * u + 3]);
+                ST(at, uint4, (make_uint4(c[2 * u], c[2 * u + 1], c[2 * u + 2], c[2 * u + 3])));
             else
-                *reinterpret_cast<uint2*>(at) = make_uint2(c[0], c[1]);
+                ST(at, uint2, (make_uint2(c[0], c[1])));
         }
     }
     if (P::w4) {
@@ -310,29 +334,31 @@ template <int BITS, int EPL> __device__ __forceinline__ void store_planes(uint8_
 #pragma unroll
         for (int u = 0; u < U; ++u) q[u] = pack_plane4<P::sh4, BITS>(c[2 * u], c[2 * u + 1]);
         uint8_t* at = base + (r.plane4 + (uint32_t)(EPL / 2) * L);
-        if (U == 4) *reinterpret_cast<uint4*>(at) = make_uint4(q[0], q[1], q[2], q[3]);
-        if (U == 2) *reinterpret_cast<uint2*>(at) = make_uint2(q[0], q[1]);
-        if (U == 1) *reinterpret_cast<uint32_t*>(at) = q[0];
+        if (U == 4) ST(at, uint4, (make_uint4(q[0], q[1], q[2], q[3])));
+        if (U == 2) ST(at, uint2, (make_uint2(q[0], q[1])));
+        if (U == 1) ST(at, uint32_t, (q[0]));
     }
     if (P::w2) {
         uint32_t q[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) q[u] = pack_plane2<P::sh2, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFFFu;
         uint8_t* at = base + (r.plane2 + (uint32_t)(EPL / 4) * L);
-        if (U == 4) *reinterpret_cast<uint2*>(at) = make_uint2(q[0] | (q[1] << 16), q[2] | (q[3] << 16));
-        if (U == 2) *reinterpret_cast<uint32_t*>(at) = q[0] | (q[1] << 16);
-        if (U == 1) *reinterpret_cast<uint16_t*>(at) = (uint16_t)q[0];
+        if (U == 4) ST(at, uint2, (make_uint2(q[0] | (q[1] << 16), q[2] | (q[3] << 16))));
+        if (U == 2) ST(at, uint32_t, (q[0] | (q[1] << 16)));
+        if (U == 1) ST(at, uint16_t, ((uint16_t)q[0]));
     }
     if (P::w1) {
         uint32_t q = 0;
 #pragma unroll
         for (int u = 0; u < U; ++u) q |= (pack_plane1<P::sh1, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFu) << (8 * u);
         uint8_t* at = base + (r.plane1 + (uint32_t)(EPL / 8) * L);
-        if (U == 4) *reinterpret_cast<uint32_t*>(at) = q;
-        if (U == 2) *reinterpret_cast<uint16_t*>(at) = (uint16_t)q;
-        if (U == 1) *at = (uint8_t)q;
+        if (U == 4) ST(at, uint32_t, (q));
+        if (U == 2) ST(at, uint16_t, ((uint16_t)q));
+        if (U == 1) ST(at, uint8_t, ((uint8_t)q));
     }
 }
+
+#undef ST
 
 template <bool SR> __device__ __forceinline__ void store_meta(uint8_t* base, const Rec& r, uint32_t g, const GroupMeta& m, uint32_t mode) {
     if (mode == kMetaInt) {

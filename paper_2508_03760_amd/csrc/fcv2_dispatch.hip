@@ -99,8 +99,8 @@ __global__ __launch_bounds__(kChunk) void k_dispatch_rank(const int32_t* __restr
     uint32_t rank = 0;
     uint64_t todo = __ballot(e >= 0);
     while (todo) {  // one round per distinct expert id in the wave; every round clears at least one lane
-        const int leader = __ffsll((unsigned long long)todo) - 1;
-        const int32_t el = __shfl(e, leader);
+        const int leader = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)todo) - 1);
+        const int32_t el = __builtin_amdgcn_readlane(e, leader);  // a scalar read, not a trip through the LDS crossbar
         const uint64_t same = __ballot(e == el);
         if (e == el) {
             rank = __popcll(same & ((1ull << lane) - 1ull));
@@ -120,16 +120,142 @@ __global__ __launch_bounds__(kChunk) void k_dispatch_rank(const int32_t* __restr
     }
 }
 
-// Quantize every token once, store the packed row K times.  `rec` holds the row's section offsets (align 16).
-// One wave tile = 2048 consecutive elements of x (rows are multiples of 32 elements, so a lane never straddles rows).
-template <int BITS, int LPG, bool SR>
+// ---- quantize-and-scatter -------------------------------------------------------------------------------------------
+// Every token is quantized once and its packed row stored K times.  `rec` holds the row's section offsets (align 16).
+// Rows are multiples of 32 elements, so a lane (32 consecutive elements) never straddles rows.
+//
+// What the copies cost is decided by how the stores meet the 128-byte lines of the send buffer: rows are 16-byte aligned
+// only, so a store instruction that writes "this wave's piece of a plane" starts and ends inside lines, and metadata
+// written by one lane in four touches a few bytes of each line.  The main kernel therefore assembles whole records in
+// LDS and copies each to its K destinations as one contiguous run whose store instructions cover 8 whole lines each,
+// with the non-temporal hint (measured on the MI355X: 160 -> 108 us for 8-bit rows of 7392 bytes).  The direct kernel
+// below it serves the shapes whose records do not fit.
+
+// Lane's share of a record, written at `o` (the record's first byte, LDS or global) through `ST`.
+template <int BITS, int LPG, bool SR, class ST>
+__device__ __forceinline__ void put_lane(const ST& st, const Rec& rec, uint32_t r, uint32_t lig, uint32_t meta_mode, const uint32_t (&c)[8],
+                                         const GroupMeta& m) {
+    using P = Planes<BITS>;
+    constexpr int U = 4;
+    uint32_t q4[U], q2[U], q1 = 0;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        q4[u] = P::w4 ? pack_plane4<P::sh4, BITS>(c[2 * u], c[2 * u + 1]) : 0u;
+        q2[u] = P::w2 ? (pack_plane2<P::sh2, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFFFu) : 0u;
+        if (P::w1) q1 |= (pack_plane1<P::sh1, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFu) << (8 * u);
+    }
+    if (P::w8) {
+        st.plane(rec.plane8 + 32u * r, make_uint4(c[0], c[1], c[2], c[3]));
+        st.plane(rec.plane8 + 32u * r + 16u, make_uint4(c[4], c[5], c[6], c[7]));
+    }
+    if (P::w4) st.plane(rec.plane4 + 16u * r, make_uint4(q4[0], q4[1], q4[2], q4[3]));
+    if (P::w2) st.plane(rec.plane2 + 8u * r, make_uint2(q2[0] | (q2[1] << 16), q2[2] | (q2[3] << 16)));
+    if (P::w1) st.plane(rec.plane1 + 4u * r, q1);
+    if (lig == 0) {
+        const uint32_t g = r / LPG;
+        if (meta_mode == kMetaInt) {
+            st.meta(rec.scale + g, (uint8_t)m.raw_s);
+            st.meta(rec.zero + g, (uint8_t)m.raw_z);
+        } else if (meta_mode == kMetaFp32) {
+            st.meta(rec.scale + 4u * g, m.s);
+            st.meta(rec.zero + 4u * g, m.lo);
+        } else {
+            st.meta(rec.scale + 2u * g, (uint16_t)(f2u(m.s) >> 16));
+            st.meta(rec.zero + 2u * g, (uint16_t)(f2u(m.lo) >> 16));
+        }
+        if (SR) {
+            st.meta(rec.spike_val + 4u * g, m.sv);
+            st.meta(rec.spike_idx + 2u * g, (uint16_t)m.si);
+        }
+    }
+}
+
+struct PutLds {  // into a record staged in LDS
+    uint8_t* o;
+    template <class V> __device__ __forceinline__ void plane(uint32_t off, V v) const { *reinterpret_cast<V*>(o + off) = v; }
+    template <class V> __device__ __forceinline__ void meta(uint32_t off, V v) const { *reinterpret_cast<V*>(o + off) = v; }
+};
+template <bool NT_META> struct PutGlobal {  // straight into the send buffer
+    uint8_t* o;
+    template <class V> __device__ __forceinline__ void plane(uint32_t off, V v) const { store_stream(o + off, v); }
+    template <class V> __device__ __forceinline__ void meta(uint32_t off, V v) const {
+        if (NT_META) store_stream(o + off, v);
+        else *reinterpret_cast<V*>(o + off) = v;
+    }
+};
+
+constexpr int kRowsBlockMax = 512;  // threads of the row-staged kernel (8 waves)
+
+// Row-staged kernel.  A block owns `rows_per_block` consecutive tokens (blockDim = their lanes rounded up to whole waves,
+// chosen on the host).  Dynamic LDS: per wave the transpose scratch | the records | the destination rows | the tables.
+template <int BITS, int LPG, bool SR, bool INT_META>
+__global__ __launch_bounds__(kRowsBlockMax) void k_dispatch_rows_t(const uint4* __restrict__ x, uint32_t T, uint32_t lanes_per_row,
+                                                                  uint32_t K, const int32_t* __restrict__ dest,
+                                                                  uint8_t* __restrict__ send, Rec rec, uint32_t row_bytes,
+                                                                  uint32_t meta_mode_arg, uint32_t rows_per_block) {
+    // integer metadata is a compile-time variant, as in the quantize kernel: it would cost the float formats registers
+    const uint32_t meta_mode = INT_META ? kMetaInt : (meta_mode_arg == kMetaFp32 ? kMetaFp32 : kMetaBf16);
+    extern __shared__ uint4 smem[];
+    const uint32_t lane = threadIdx.x & 63;
+    const uint32_t wave = (uint32_t)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const uint32_t n_waves = blockDim.x >> 6;
+    uint4* scratch = smem + wave * (64 * kRowU4);
+    uint4* recs = smem + n_waves * (64 * kRowU4);
+    const uint32_t row_pieces = row_bytes >> 4;
+    int32_t* drow = reinterpret_cast<int32_t*>(recs + rows_per_block * row_pieces);
+    float* tabs = reinterpret_cast<float*>(drow + rows_per_block * K);
+    const uint32_t row0 = blockIdx.x * rows_per_block;
+    const uint32_t rows_here = min(rows_per_block, T - row0);
+    const uint32_t block_lanes = rows_here * lanes_per_row;
+    for (uint32_t i = threadIdx.x; i < rows_here * K; i += blockDim.x) drow[i] = dest[row0 * K + i];
+    // the padding between a record's sections travels with the copies: it is written as zero
+    for (uint32_t i = threadIdx.x; i < rows_here * row_pieces; i += blockDim.x) recs[i] = make_uint4(0, 0, 0, 0);
+    if (INT_META) {
+        for (uint32_t t = threadIdx.x; t < (uint32_t)kScaleTablePow; t += blockDim.x) tabs[t] = scale_table_pow((int)t);
+        for (uint32_t t = threadIdx.x; t < (uint32_t)kScaleTableThr; t += blockDim.x) tabs[kScaleTablePow + t] = scale_table_thr((int)t);
+    }
+    __syncthreads();
+    if (wave * 64 < block_lanes) {  // whole waves past the block's last row only help with the copies
+        const uint32_t piece0 = (row0 * lanes_per_row + wave * 64) * 4;
+        const TileIn in = tile_load(x, piece0, lane, (block_lanes - wave * 64) * 4);
+        uint32_t w[16];
+        tile_transpose(in, scratch, lane, w);
+        const uint32_t l = wave * 64 + lane;
+        uint32_t c[8];
+        GroupMeta m;
+        quantize_lane<BITS, kEplStream, LPG, SR>(w, lane & (LPG - 1), meta_mode, tabs, &scratch[lane * kRowU4], c, m);
+        if (l < block_lanes) {
+            const uint32_t rl = l / lanes_per_row;
+            put_lane<BITS, LPG, SR>(PutLds{reinterpret_cast<uint8_t*>(recs + rl * row_pieces)}, rec, l - rl * lanes_per_row,
+                                    lane & (LPG - 1), meta_mode, c, m);
+        }
+    }
+    __syncthreads();
+    // Copies.  One unit = 64 consecutive 16-byte pieces of one copy, cut so that a unit starts on a line of the send
+    // buffer (the first unit of a copy starts up to 7 pieces before the record and masks them off).
+    const uint32_t n_seg = (row_pieces + 7 + 63) >> 6;
+    const uint32_t units = rows_here * K * n_seg;
+    for (uint32_t u = wave; u < units; u += n_waves) {
+        const uint32_t rk = u / n_seg, j = u - rk * n_seg;
+        const int32_t d = drow[rk];
+        if (d < 0) continue;
+        const uint32_t ro = __umul24((uint32_t)d, row_bytes);  // 32-bit offsets: checked on the host
+        const uint32_t shift = (uint32_t)((reinterpret_cast<uintptr_t>(send) + ro) >> 4) & 7u;
+        const int32_t p = (int32_t)(j * 64 + lane) - (int32_t)shift;
+        if (p >= 0 && (uint32_t)p < row_pieces) store_stream(send + (ro + 16u * (uint32_t)p), recs[(rk / K) * row_pieces + (uint32_t)p]);
+    }
+}
+
+// Direct kernel: one wave tile = 2048 consecutive elements of x, every lane stores its share of the K copies itself.
+template <int BITS, int LPG, bool SR, bool INT_META>
 __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __restrict__ x, uint32_t n_lanes, uint32_t lanes_per_row,
                                                              uint32_t K, const int32_t* __restrict__ dest, uint8_t* __restrict__ send,
-                                                             Rec rec, uint32_t row_bytes, uint32_t meta_mode) {
+                                                             Rec rec, uint32_t row_bytes, uint32_t meta_mode_arg) {
+    const uint32_t meta_mode = INT_META ? kMetaInt : (meta_mode_arg == kMetaFp32 ? kMetaFp32 : kMetaBf16);
     constexpr int EPL = kEplStream;
     __shared__ uint4 lds[kWaves][64 * kRowU4];
     __shared__ float tabs[kScaleTables];
-    if (meta_mode == kMetaInt) fill_scale_tables(tabs);
+    if (INT_META) fill_scale_tables(tabs);
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const uint32_t lig = lane & (LPG - 1);
     const uint32_t tile = blockIdx.x * kWaves + wave;
@@ -144,21 +270,6 @@ __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __rest
     uint32_t c[EPL / 4];
     GroupMeta m;
     quantize_lane<BITS, EPL, LPG, SR>(w, lig, meta_mode, tabs, &lds[wave][lane * kRowU4], c, m);
-    const uint32_t g = r / LPG;
-    // The send buffer is addressed with 32-bit offsets (checked on the host): a row's offset is one 24-bit multiply,
-    // every store one add on top of per-lane offsets computed once.
-    using P = Planes<BITS>;
-    constexpr int U = EPL / 8;
-    uint32_t q4[U], q2[U], q1 = 0;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        q4[u] = P::w4 ? pack_plane4<P::sh4, BITS>(c[2 * u], c[2 * u + 1]) : 0u;
-        q2[u] = P::w2 ? (pack_plane2<P::sh2, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFFFu) : 0u;
-        if (P::w1) q1 |= (pack_plane1<P::sh1, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFu) << (8 * u);
-    }
-    const uint32_t o8 = rec.plane8 + 32u * r, o4 = rec.plane4 + 16u * r, o2 = rec.plane2 + 8u * r, o1 = rec.plane1 + 4u * r;
-    const uint32_t msz = (meta_mode == kMetaFp32) ? 4u : (meta_mode == kMetaInt) ? 1u : 2u;
-    const uint32_t os = rec.scale + msz * g, oz = rec.zero + msz * g, ov = rec.spike_val + 4u * g, oi = rec.spike_idx + 2u * g;
     for (uint32_t k0 = 0; k0 < K; k0 += 8) {
         int32_t rows[8];  // all destinations first: the loads overlap instead of queueing one behind the other
 #pragma unroll
@@ -166,44 +277,61 @@ __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __rest
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             if (rows[i] < 0) continue;
-            const uint32_t ro = __umul24((uint32_t)rows[i], row_bytes);
-            if (P::w8) {
-                *reinterpret_cast<uint4*>(send + (ro + o8)) = make_uint4(c[0], c[1], c[2], c[3]);
-                *reinterpret_cast<uint4*>(send + (ro + o8 + 16u)) = make_uint4(c[4], c[5], c[6], c[7]);
-            }
-            if (P::w4) *reinterpret_cast<uint4*>(send + (ro + o4)) = make_uint4(q4[0], q4[1], q4[2], q4[3]);
-            if (P::w2) *reinterpret_cast<uint2*>(send + (ro + o2)) = make_uint2(q2[0] | (q2[1] << 16), q2[2] | (q2[3] << 16));
-            if (P::w1) *reinterpret_cast<uint32_t*>(send + (ro + o1)) = q1;
-            if (lig == 0) {
-                if (meta_mode == kMetaInt) {
-                    send[ro + os] = (uint8_t)m.raw_s;
-                    send[ro + oz] = (uint8_t)m.raw_z;
-                } else if (meta_mode == kMetaFp32) {
-                    *reinterpret_cast<float*>(send + (ro + os)) = m.s;
-                    *reinterpret_cast<float*>(send + (ro + oz)) = m.lo;
-                } else {
-                    *reinterpret_cast<uint16_t*>(send + (ro + os)) = (uint16_t)(f2u(m.s) >> 16);
-                    *reinterpret_cast<uint16_t*>(send + (ro + oz)) = (uint16_t)(f2u(m.lo) >> 16);
-                }
-                if (SR) {
-                    *reinterpret_cast<uint32_t*>(send + (ro + ov)) = m.sv;
-                    *reinterpret_cast<uint16_t*>(send + (ro + oi)) = (uint16_t)m.si;
-                }
-            }
+            // the hint pays for metadata only where every lane stores (groups of 32)
+            put_lane<BITS, LPG, SR>(PutGlobal<LPG == 1>{send + __umul24((uint32_t)rows[i], row_bytes)}, rec, r, lig, meta_mode, c, m);
         }
     }
 }
 
+// Rows per block and block size of the row-staged kernel for rows of `lpr` lanes; {0, 0} if the shape does not fit it.
+struct RowsPlan {
+    uint32_t rows, threads;
+    size_t lds_bytes;
+};
+static RowsPlan rows_plan(uint32_t lpr, uint32_t K, uint32_t row_bytes, bool int_meta) {
+    RowsPlan best = {0, 0, 0};
+    uint32_t best_idle = ~0u;
+    for (uint32_t R = 1; R <= 8 && R * lpr <= (uint32_t)kRowsBlockMax; ++R) {
+        const uint32_t waves = (R * lpr + 63) / 64;
+        const size_t lds = (size_t)waves * 64 * kRowU4 * 16 + (size_t)R * row_bytes + (size_t)R * K * 4 + (int_meta ? kScaleTables * 4 : 0);
+        if (lds > 64 * 1024) break;
+        const uint32_t idle = (waves * 64 - R * lpr) * 1024 / (waves * 64);  // idle lanes, in 1/1024 of the block
+        if (idle < best_idle) {
+            best_idle = idle;
+            best = {R, waves * 64, lds};
+        }
+    }
+    return best;
+}
+
 template <int BITS, int G, bool SR> struct LaunchDispatch {
-    static int run(const void* x, uint64_t n, uint32_t H, uint32_t K, const int32_t* dest, uint8_t* send, const Rec& rec,
+    static int run(const void* x, uint32_t T, uint32_t H, uint32_t K, const int32_t* dest, uint8_t* send, const Rec& rec,
                    uint32_t row_bytes, uint32_t meta_mode, hipStream_t st) {
-        constexpr int EPL = kEplStream;
-        const uint32_t n_lanes = (uint32_t)(n / EPL);
-        hipLaunchKernelGGL((k_dispatch_quant_t<BITS, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
-                           (const uint4*)x, n_lanes, H / EPL, K, dest, send, rec, row_bytes, meta_mode);
+        constexpr int EPL = kEplStream, LPG = G / EPL;
+        const uint32_t lpr = H / EPL, n_lanes = T * lpr;
+        const bool im = meta_mode == kMetaInt;
+        const RowsPlan plan = rows_plan(lpr, K, row_bytes, im);
+        if (plan.rows) {
+            const dim3 grid((T + plan.rows - 1) / plan.rows), block(plan.threads);
+            if (im)
+                hipLaunchKernelGGL((k_dispatch_rows_t<BITS, LPG, SR, true>), grid, block, plan.lds_bytes, st, (const uint4*)x, T, lpr, K,
+                                   dest, send, rec, row_bytes, meta_mode, plan.rows);
+            else
+                hipLaunchKernelGGL((k_dispatch_rows_t<BITS, LPG, SR, false>), grid, block, plan.lds_bytes, st, (const uint4*)x, T, lpr, K,
+                                   dest, send, rec, row_bytes, meta_mode, plan.rows);
+        } else {
+            const dim3 grid(grid_lanes(n_lanes)), block(kBlock);
+            if (im)
+                hipLaunchKernelGGL((k_dispatch_quant_t<BITS, LPG, SR, true>), grid, block, 0, st, (const uint4*)x, n_lanes, lpr, K, dest,
+                                   send, rec, row_bytes, meta_mode);
+            else
+                hipLaunchKernelGGL((k_dispatch_quant_t<BITS, LPG, SR, false>), grid, block, 0, st, (const uint4*)x, n_lanes, lpr, K, dest,
+                                   send, rec, row_bytes, meta_mode);
+        }
         return launch_status();
     }
 };
+
 
 int launch_dispatch(const fcv2_fmt_t* fmt, const void* x, const int32_t* ids, uint32_t T, uint32_t H, uint32_t K, uint32_t E,
                     uint8_t* send, int32_t* expert_offsets, int32_t* row_src, void* ws, const Rec& rec, uint32_t row_bytes,
@@ -217,7 +345,7 @@ int launch_dispatch(const fcv2_fmt_t* fmt, const void* x, const int32_t* ids, ui
     hipLaunchKernelGGL(k_dispatch_rank, dim3(w.n_chunks), dim3(kChunk), (kChunk / 64 + 1) * E * 4, st, ids, w.n_slots, E, hist,
                        (const int32_t*)totals, expert_offsets, dest, row_src);
     if (launch_status() != FCV2_OK) return FCV2_ERR_LAUNCH;
-    return by_format<LaunchDispatch>(fmt, x, (uint64_t)T * H, H, K, (const int32_t*)dest, send, rec, row_bytes, meta_mode_of(fmt), st);
+    return by_format<LaunchDispatch>(fmt, x, T, H, K, (const int32_t*)dest, send, rec, row_bytes, meta_mode_of(fmt), st);
 }
 
 }  // namespace fcv2

@@ -73,7 +73,7 @@ __global__ __launch_bounds__(kBlock) void k_unpack_dequant_t(PeerPtrs records, u
 #pragma unroll
     for (int k = 0; k < NP; ++k) {
         const uint32_t P = k * 64 + lane;
-        if (piece0 + P < n_pieces) out[(uint64_t)piece0 + P] = lds[wave][(P / NP) * ROW + (P % NP)];
+        if (piece0 + P < n_pieces) store_stream(&out[(uint64_t)piece0 + P], lds[wave][(P / NP) * ROW + (P % NP)]);
     }
 }
 

@@ -423,6 +423,38 @@ def test_dispatch_quant_nine_copies_per_token():
     check_dispatch(x, ids, E, 5, 64, SR, "dispatch K=9 b5")
 
 
+@pytest.mark.parametrize("bits,group,flags", [(2, 128, SR), (8, 32, SR), (4, 64, SR | INT), (5, 256, F32)])
+def test_dispatch_quant_rows_beyond_one_block(bits, group, flags):
+    """Rows too long for a block to hold a whole record (32,768 elements = 1,024 lanes), and one length that just fits
+    (16,384): two code paths, one result."""
+    for T, H in ((5, 32768), (7, 16384)):
+        K, E = 3, 7
+        x = W.tensor(3, 5, rows=T, cols=H)
+        ids = W.topk_routing(W.seed_for(3) + 4, T, E, K)
+        ids[1, 1] = -1
+        check_dispatch(x, ids, E, bits, group, flags, f"dispatch long rows H{H} b{bits} g{group} f{flags}")
+
+
+def test_dispatch_quant_send_buffer_off_the_line_grid():
+    """The copies are cut on 128-byte lines of the send buffer: every 16-byte phase of the buffer's address gives the
+    same bytes."""
+    T, H, K, E = 50, 1024, 2, 5
+    bits, group, flags = 3, 128, SR
+    x = W.tensor(3, 6, rows=T, cols=H)
+    ids = W.topk_routing(W.seed_for(3) + 5, T, E, K)
+    want, _, _ = O.dispatch_quant(x, ids, E, bits, group, flags)
+    L = fcv2.get_layout(H, bits, group, flags, fcv2.ROW_ALIGN)
+    xd, idd = to_dev_bf16(x).view(T, H), torch.from_numpy(ids).to(DEV)
+    for phase in range(8):
+        back = torch.zeros(T * K * L.total_bytes + 256, dtype=torch.uint8, device=DEV)
+        base = (-back.data_ptr()) % 128 + 16 * phase
+        send = back[base:base + T * K * L.total_bytes].view(T * K, L.total_bytes)
+        fcv2.dispatch_quant(xd, idd, E, bits, group, flags, send_buf=send)
+        got = send.cpu().numpy()[:want.shape[0]]
+        assert np.array_equal(got, want), f"phase {phase}"
+        assert int(back[:base].max() if base else 0) == 0 and int(back[base + T * K * L.total_bytes:].max()) == 0, f"phase {phase}: wrote outside"
+
+
 def test_dispatch_quant_degenerate_routing():
     T, H, K, E = 130, 512, 8, 256
     x = W.tensor(3, 1, rows=T, cols=H)
