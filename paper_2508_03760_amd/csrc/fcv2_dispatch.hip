@@ -145,8 +145,7 @@ __device__ __forceinline__ void put_lane(const ST& st, const Rec& rec, uint32_t 
         if (P::w1) q1 |= (pack_plane1<P::sh1, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFu) << (8 * u);
     }
     if (P::w8) {
-        st.plane(rec.plane8 + 32u * r, make_uint4(c[0], c[1], c[2], c[3]));
-        st.plane(rec.plane8 + 32u * r + 16u, make_uint4(c[4], c[5], c[6], c[7]));
+        st.halves(rec.plane8 + 32u * r, make_uint4(c[0], c[1], c[2], c[3]), make_uint4(c[4], c[5], c[6], c[7]));
     }
     if (P::w4) st.plane(rec.plane4 + 16u * r, make_uint4(q4[0], q4[1], q4[2], q4[3]));
     if (P::w2) st.plane(rec.plane2 + 8u * r, make_uint2(q2[0] | (q2[1] << 16), q2[2] | (q2[3] << 16)));
@@ -174,6 +173,10 @@ struct PutLds {  // into a record staged in LDS
     uint8_t* o;
     template <class V> __device__ __forceinline__ void plane(uint32_t off, V v) const { *reinterpret_cast<V*>(o + off) = v; }
     template <class V> __device__ __forceinline__ void meta(uint32_t off, V v) const { *reinterpret_cast<V*>(o + off) = v; }
+    __device__ __forceinline__ void halves(uint32_t off, uint4 a, uint4 b) const {
+        plane(off, a);
+        plane(off + 16u, b);
+    }
 };
 template <bool NT_META> struct PutGlobal {  // straight into the send buffer
     uint8_t* o;
@@ -182,12 +185,17 @@ template <bool NT_META> struct PutGlobal {  // straight into the send buffer
         if (NT_META) store_stream(o + off, v);
         else *reinterpret_cast<V*>(o + off) = v;
     }
+    // a lane's 32 bytes of the 8-bit plane as two stores 32 bytes apart per lane: half lines, so no hint
+    __device__ __forceinline__ void halves(uint32_t off, uint4 a, uint4 b) const {
+        *reinterpret_cast<uint4*>(o + off) = a;
+        *reinterpret_cast<uint4*>(o + off + 16u) = b;
+    }
 };
 
 constexpr int kRowsBlockMax = 512;  // threads of the row-staged kernel (8 waves)
 
 // Row-staged kernel.  A block owns `rows_per_block` consecutive tokens (blockDim = their lanes rounded up to whole waves,
-// chosen on the host).  Dynamic LDS: per wave the transpose scratch | the records | the destination rows | the tables.
+// chosen on the host: the count up to 64 that leaves the fewest idle lanes; 1 and 2 rows measure the same at H = 7168).  Dynamic LDS: per wave the transpose scratch | the records | the destination rows | the tables.
 template <int BITS, int LPG, bool SR, bool INT_META>
 __global__ __launch_bounds__(kRowsBlockMax) void k_dispatch_rows_t(const uint4* __restrict__ x, uint32_t T, uint32_t lanes_per_row,
                                                                   uint32_t K, const int32_t* __restrict__ dest,
@@ -291,7 +299,7 @@ struct RowsPlan {
 static RowsPlan rows_plan(uint32_t lpr, uint32_t K, uint32_t row_bytes, bool int_meta) {
     RowsPlan best = {0, 0, 0};
     uint32_t best_idle = ~0u;
-    for (uint32_t R = 1; R <= 8 && R * lpr <= (uint32_t)kRowsBlockMax; ++R) {
+    for (uint32_t R = 1; R <= 64 && R * lpr <= (uint32_t)kRowsBlockMax; ++R) {
         const uint32_t waves = (R * lpr + 63) / 64;
         const size_t lds = (size_t)waves * 64 * kRowU4 * 16 + (size_t)R * row_bytes + (size_t)R * K * 4 + (int_meta ? kScaleTables * 4 : 0);
         if (lds > 64 * 1024) break;

@@ -435,6 +435,17 @@ def test_dispatch_quant_rows_beyond_one_block(bits, group, flags):
         check_dispatch(x, ids, E, bits, group, flags, f"dispatch long rows H{H} b{bits} g{group} f{flags}")
 
 
+@pytest.mark.parametrize("H,group", [(32, 32), (64, 32), (96, 32), (256, 128), (2560, 256)])
+def test_dispatch_quant_short_and_odd_rows(H, group):
+    """Rows of one to a few lanes (many tokens per block, the last block short) and a row length that leaves idle lanes."""
+    T, K, E = 203, 2, 9
+    x = W.tensor(3, 7, rows=T, cols=H)
+    ids = W.topk_routing(W.seed_for(3) + 6, T, E, K)
+    ids[0, 0] = -1
+    check_dispatch(x, ids, E, 4, group, SR, f"dispatch H{H} g{group}")
+    check_dispatch(x, ids, E, 2, group, INT, f"dispatch H{H} g{group} int")
+
+
 def test_dispatch_quant_send_buffer_off_the_line_grid():
     """The copies are cut on 128-byte lines of the send buffer: every 16-byte phase of the buffer's address gives the
     same bytes."""
