@@ -248,9 +248,19 @@ __global__ __launch_bounds__(kRowsBlockMax) void k_dispatch_rows_t(const uint4* 
         const int32_t d = drow[rk];
         if (d < 0) continue;
         const uint32_t ro = __umul24((uint32_t)d, row_bytes);  // 32-bit offsets: checked on the host
-        const uint32_t shift = (uint32_t)((reinterpret_cast<uintptr_t>(send) + ro) >> 4) & 7u;
+        const uint32_t a0 = (uint32_t)(reinterpret_cast<uintptr_t>(send) >> 4) + (ro >> 4);  // the copy's first piece, counted in pieces
+        const uint32_t shift = a0 & 7u;
         const int32_t p = (int32_t)(j * 64 + lane) - (int32_t)shift;
-        if (p >= 0 && (uint32_t)p < row_pieces) store_stream(send + (ro + 16u * (uint32_t)p), recs[(rk / K) * row_pieces + (uint32_t)p]);
+        if (p >= 0 && (uint32_t)p < row_pieces) {
+            const uint4 v = recs[(rk / K) * row_pieces + (uint32_t)p];
+            uint8_t* at = send + (ro + 16u * (uint32_t)p);
+            // The line a copy starts in and the line it ends in are shared with the neighbouring rows, which other blocks
+            // write: those pieces go out as ordinary stores, so that the halves of such a line meet in the cache.
+            const uint32_t line = (a0 + (uint32_t)p) >> 3, end = a0 + row_pieces;
+            const bool shared = (shift != 0 && line == (a0 >> 3)) || ((end & 7u) != 0 && line == (end >> 3));
+            if (shared) *reinterpret_cast<uint4*>(at) = v;
+            else store_stream(at, v);
+        }
     }
 }
 
