@@ -89,8 +89,10 @@ def main():
         return dict(quantize_pack=2 * n + P, reduce_requant=(n_peers + 1) * P, unpack_dequant=P + 2 * n)
 
     def n_sets_for(bits):
-        per_set = 2 * n * 2 + (n_peers + 2) * packed_bytes(n, bits, group)
-        return max(8, -(-3 * LLC_BYTES // per_set))
+        """Buffer sets to rotate: enough that even the kernel with the smallest footprint per set, timed alone, cycles
+        through three times the last-level cache before it sees a set again."""
+        smallest = min(algo_bytes(bits).values())
+        return max(8, -(-3 * LLC_BYTES // smallest))
 
     def bind_calls(sets, bits):
         """Arguments marshalled once per buffer set: a timed loop is C-ABI calls and nothing else."""
