@@ -169,23 +169,25 @@ def main():
                        gbs=round(ab[k] / (kern_ms[k] * 1e-3) / 1e9, 1),
                        frac_of_hbm_peak=round(ab[k] / (kern_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)) for k in ab}
     dom = "reduce_requant"
-    roofline = dict(bound="hbm", kernel=f"k_reduce_requant<3, 16, 8, true> ({dom}, N={n_peers})",
-                    achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(kernels[dom]["gbs"] / HBM_PEAK_GBS, 4), traffic=TRAFFIC_BYTES[dom],
-                    traffic_source="profiles/headline_step_b3_g128_n8.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scaled by a copy of known size)")
-    # the same kernel against the bound that actually limits it at 3 bits: VALU issue
-    # executed = VALU instructions per output element as counted by rocprofv3; algorithmic = what the definition itself
-    # needs per output element at N peers: per peer-element extract + FMA + add, per output element bf16 rounding (1/2),
-    # order key, two running top-2 selections (2 x 2), subtract, multiply, convert, pack
+    kname = f"k_reduce_requant<3, 16, 8, true> ({dom}, N={n_peers})"
+    traffic_source = "profiles/headline_step_b3_g128_n8.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scaled by a copy of known size)"
+    # The dominant kernel against HBM, the bound the benchmark's metric is stated in ...
+    hbm_roofline = dict(bound="hbm", kernel=kname, achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=round(kernels[dom]["gbs"] / HBM_PEAK_GBS, 4), traffic=TRAFFIC_BYTES[dom], traffic_source=traffic_source)
+    # ... and against the bound that limits it: VALU issue (rocprofv3: the VALUs issue in 98 % of its cycles).
+    # achieved = algorithmic lane-operations per output element x elements / duration, where algorithmic = what the
+    # definition itself needs at N peers: per peer-element extract + FMA + add, per output element bf16 rounding (1/2),
+    # order key, two running top-2 selections (2 x 2), subtract, multiply, convert, pack.  executed = VALU instructions
+    # per output element as counted by rocprofv3 (SQ_INSTS_VALU): unpacking split planes, metadata, spike patching and
+    # cross-lane merges come on top of the algorithmic count.
     algo_ops = 3.0 * n_peers + 9.5
-    alu = dict(bound="alu", unit="T lane-op/s", peak=ALU_PEAK_TLOPS,
-               executed_ops_per_element=VALU_OPS_PER_ELEMENT[dom], algorithmic_ops_per_element=algo_ops,
-               achieved=round(VALU_OPS_PER_ELEMENT[dom] * n / (kern_ms[dom] * 1e-3) / 1e12, 2),
-               achieved_algorithmic=round(algo_ops * n / (kern_ms[dom] * 1e-3) / 1e12, 2),
-               note="executed: VALU instructions per output element (rocprofv3 SQ_INSTS_VALU) x elements / duration; "
-                    "peak = 256 CU x 4 SIMD x 16 lanes x 2.4 GHz without packed fp32")
-    alu["frac"] = round(alu["achieved"] / ALU_PEAK_TLOPS, 4)
-    alu["frac_algorithmic"] = round(alu["achieved_algorithmic"] / ALU_PEAK_TLOPS, 4)
+    ops_s = lambda per_elem: per_elem * n / (kern_ms[dom] * 1e-3) / 1e12
+    roofline = dict(bound="alu", kernel=kname, achieved=round(ops_s(algo_ops), 2), peak=round(ALU_PEAK_TLOPS, 2),
+                    unit="T lane-op/s", frac=round(ops_s(algo_ops) / ALU_PEAK_TLOPS, 4), traffic=TRAFFIC_BYTES[dom],
+                    traffic_source=traffic_source, algorithmic_ops_per_element=algo_ops,
+                    executed_ops_per_element=VALU_OPS_PER_ELEMENT[dom], executed=round(ops_s(VALU_OPS_PER_ELEMENT[dom]), 2),
+                    frac_executed=round(ops_s(VALU_OPS_PER_ELEMENT[dom]) / ALU_PEAK_TLOPS, 4),
+                    peak_note="256 CU x 4 SIMD x 16 lanes x 2.4 GHz, no packed fp32; traffic = HBM bytes per launch")
     # practical streaming ceiling: the library's plain copy kernel on 1 GiB (source and destination together are eight
     # times the 256 MB last-level cache, so this is an HBM figure)
     import ctypes as C
@@ -525,7 +527,7 @@ def main():
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "warm_cache_gbs": round(total_bytes / (ms_warm * 1e-3) / 1e9, 1),
         "copy_ceiling_gbs": round(copy_gbs, 1), "copy_same_size_as_quantize_pack": copy_same_size,
-        "kernels": kernels, "roofline": roofline, "alu_roofline": alu, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
+        "kernels": kernels, "roofline": roofline, "hbm_roofline": hbm_roofline, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
         "quality_proxy_sqnr": quality, "low_bit_default_shape_g32": low_bit, "two_step_allreduce_rank_share": two_step, "micro_chunk_pipelining": pipelined, "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
     }
     print(json.dumps(out))
