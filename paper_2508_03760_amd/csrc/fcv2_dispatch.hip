@@ -128,8 +128,8 @@ __global__ __launch_bounds__(kChunk) void k_dispatch_rank(const int32_t* __restr
 // only, so a store instruction that writes "this wave's piece of a plane" starts and ends inside lines, and metadata
 // written by one lane in four touches a few bytes of each line.  The main kernel therefore assembles whole records in
 // LDS and copies each to its K destinations as one contiguous run whose store instructions cover 8 whole lines each,
-// with the non-temporal hint (measured on the MI355X: 160 -> 108 us for 8-bit rows of 7392 bytes).  The direct kernel
-// below it serves the shapes whose records do not fit.
+// with the non-temporal hint (measured on the MI355X, 65,536 copies: 2-bit rows of 2,352 bytes 83 -> 58 us for the whole
+// call, 8-bit rows of 7,728 bytes 174 -> 119 us).  The direct kernel below it serves the shapes whose records do not fit.
 
 // Lane's share of a record, written at `o` (the record's first byte, LDS or global) through `ST`.
 template <int BITS, int LPG, bool SR, class ST>
@@ -195,7 +195,8 @@ template <bool NT_META> struct PutGlobal {  // straight into the send buffer
 constexpr int kRowsBlockMax = 512;  // threads of the row-staged kernel (8 waves)
 
 // Row-staged kernel.  A block owns `rows_per_block` consecutive tokens (blockDim = their lanes rounded up to whole waves,
-// chosen on the host: the count up to 64 that leaves the fewest idle lanes; 1 and 2 rows measure the same at H = 7168).  Dynamic LDS: per wave the transpose scratch | the records | the destination rows | the tables.
+// chosen on the host: the count up to 64 that leaves the fewest idle lanes; 1 and 2 rows measure the same at H = 7168).
+// Dynamic LDS: per wave the transpose scratch | the records | the destination rows | the tables.
 template <int BITS, int LPG, bool SR, bool INT_META>
 __global__ __launch_bounds__(kRowsBlockMax) void k_dispatch_rows_t(const uint4* __restrict__ x, uint32_t T, uint32_t lanes_per_row,
                                                                   uint32_t K, const int32_t* __restrict__ dest,
