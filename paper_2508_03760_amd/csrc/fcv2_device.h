@@ -259,7 +259,9 @@ __device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint
             for (int b = 0; b < 4; ++b) {
                 const int j = 4 * i + b;
                 const float x = u2f((j & 1) ? (w[j >> 1] & 0xFFFF0000u) : (w[j >> 1] << 16));
-                cc = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fminf(__fmul_rn(__fsub_rn(x, off), inv), (float)QMAX), b, cc);
+                // median of (t, 0, qmax): the clamp, and 0 for a NaN (a sum over peers of which one decodes to NaN),
+                // where a plain minimum with qmax would return qmax
+                cc = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_amdgcn_fmed3f(__fmul_rn(__fsub_rn(x, off), inv), 0.0f, (float)QMAX), b, cc);
             }
             c[i] = cc;
         }

@@ -239,6 +239,31 @@ def test_reduce_requant_all_formats(bits, group):
     check_reduce(xs[:5], bits, group, SR | INT, f"b{bits} g{group} N5 integer metadata")
 
 
+@pytest.mark.parametrize("flags_in", [0, SR, SR | F32])
+def test_reduce_requant_of_sums_that_are_not_numbers(flags_in):
+    """A peer whose values span more than the fp32 range is packed with an infinite scale and decodes to NaN (the
+    documented behaviour of the sender); sums with it are NaN, sums of the largest finite values are infinite.  The
+    requantized record still matches the oracle in every output format: a NaN takes code 0."""
+    group, n = 128, 2048 + 256
+    rng = np.random.default_rng(17)
+    v = np.clip(rng.standard_normal(n) * 3e38, -3.3e38, 3.3e38).astype(np.float32)
+    v[n // 2:] = rng.standard_normal(n - n // 2)  # only the first half of this peer decodes to NaN
+    huge = W.f32_to_bf16_bits(v)
+    big = W.f32_to_bf16_bits(np.where(np.arange(n) % 256 < 128, 3.0e38, 1.0).astype(np.float32))  # finite ranges, infinite sums
+    xs = [W.tensor(2, 0, rows=1, cols=n).reshape(-1), huge, big, big, W.tensor(2, 1, rows=1, cols=n).reshape(-1)]
+    for bits_in, bits_out, flags_out in ((4, 2, INT), (4, 3, SR | INT), (3, 5, SR | INT), (8, 8, INT), (5, 4, SR), (2, 6, F32)):
+        fin, fout = (bits_in, group, flags_in), (bits_out, group, (flags_out & ~SR) | (flags_in & SR))
+        peers_o = [O.quantize_pack(x, *fin) for x in xs]
+        want, s_want = O.reduce_requant(peers_o, n, fin, fout, want_sum=True)
+        assert np.isnan(s_want).any() and np.isinf(s_want).any()
+        got, s_got = fcv2.reduce_requant([torch.from_numpy(p).to(DEV) for p in peers_o], n, fin, fout, want_sum=True)
+        sg = s_got.cpu().numpy()
+        assert np.array_equal(np.isnan(sg), np.isnan(s_want)), f"{fin} -> {fout}: NaN positions"
+        ok = ~np.isnan(s_want)
+        assert np.array_equal(sg[ok].view(np.uint32), s_want[ok].view(np.uint32)), f"{fin} -> {fout}: sums"
+        assert_packed_equal(got.cpu().numpy(), want, O.get_layout(n, *fout), fout[2], f"reduce of NaN sums {fin} -> {fout}")
+
+
 @pytest.mark.parametrize("n_peers", [1, 2, 5, 16])
 def test_reduce_requant_peer_counts(n_peers):
     n = 4096 + 256
