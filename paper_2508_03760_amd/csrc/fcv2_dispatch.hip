@@ -302,26 +302,7 @@ __global__ __launch_bounds__(kBlock) void k_dispatch_quant_t(const uint4* __rest
     }
 }
 
-// Rows per block and block size of the row-staged kernel for rows of `lpr` lanes; {0, 0} if the shape does not fit it.
-struct RowsPlan {
-    uint32_t rows, threads;
-    size_t lds_bytes;
-};
-static RowsPlan rows_plan(uint32_t lpr, uint32_t K, uint32_t row_bytes, bool int_meta) {
-    RowsPlan best = {0, 0, 0};
-    uint32_t best_idle = ~0u;
-    for (uint32_t R = 1; R <= 64 && R * lpr <= (uint32_t)kRowsBlockMax; ++R) {
-        const uint32_t waves = (R * lpr + 63) / 64;
-        const size_t lds = (size_t)waves * 64 * kRowU4 * 16 + (size_t)R * row_bytes + (size_t)R * K * 4 + (int_meta ? kScaleTables * 4 : 0);
-        if (lds > 64 * 1024) break;
-        const uint32_t idle = (waves * 64 - R * lpr) * 1024 / (waves * 64);  // idle lanes, in 1/1024 of the block
-        if (idle < best_idle) {
-            best_idle = idle;
-            best = {R, waves * 64, lds};
-        }
-    }
-    return best;
-}
+static_assert(64 * kRowU4 * 16 == kWaveScratchBytes && kRowsBlockMax == kRowsPlanThreadsMax, "the launch plan and the kernel disagree");
 
 template <int BITS, int G, bool SR> struct LaunchDispatch {
     static int run(const void* x, uint32_t T, uint32_t H, uint32_t K, const int32_t* dest, uint8_t* send, const Rec& rec,

@@ -143,6 +143,14 @@ void hc_scale_int_from_tables(uint32_t first_bits, uint32_t count, int8_t* k, ui
 int hc_scale_int_estimate(float s) { return scale_int_estimate(s); }
 float hc_scale_of_int(int k) { return scale_of_int(k); }
 
+// Launch plan of the row-staged dispatch kernel: out3 = {rows per block, threads, LDS bytes}.
+void hc_rows_plan(uint32_t lpr, uint32_t K, uint32_t row_bytes, int int_meta, uint64_t* out3) {
+    const RowsPlan p = rows_plan(lpr, K, row_bytes, int_meta != 0);
+    out3[0] = p.rows;
+    out3[1] = p.threads;
+    out3[2] = p.lds_bytes;
+}
+
 uint32_t hc_key_of_bf16(uint32_t u) { return key_of_bf16(u); }
 uint32_t hc_bf16_of_key(uint32_t k) { return bf16_of_key(k); }
 uint32_t hc_bf16_rne_bits(uint32_t u) { return bf16_rne_bits(u); }
