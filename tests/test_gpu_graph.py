@@ -73,3 +73,50 @@ def test_step_replays_under_graph_capture(bits, group, flags):
             peers_o = [O.quantize_pack(h, *fmt) for h in hosts]
             want = O.unpack_dequant(O.reduce_requant(peers_o, n, fmt), n, *fmt, O.DT_BF16)
             assert np.array_equal(o.view(torch.int16).cpu().numpy().view(np.uint16), want)
+
+
+def test_dispatch_replays_under_graph_capture():
+    """fcv2_dispatch_quant is four launches on the caller's stream and nothing else: recorded once, replayed with new
+    tokens and new routing in the same buffers, every replay equals the eager call and the oracle."""
+    T, H, K, E = 96, 2048, 4, 12
+    bits, group, flags = 2, 128, SR
+    L = fcv2.get_layout(H, bits, group, flags, fcv2.ROW_ALIGN)
+    x = torch.zeros((T, H), dtype=torch.bfloat16, device=DEV)
+    ids = torch.zeros((T, K), dtype=torch.int32, device=DEV)
+
+    def bufs():
+        return dict(send_buf=torch.zeros((T * K, L.total_bytes), dtype=torch.uint8, device=DEV),
+                    expert_offsets=torch.zeros(E + 1, dtype=torch.int32, device=DEV),
+                    row_src=torch.zeros(T * K, dtype=torch.int32, device=DEV),
+                    workspace=torch.empty(fcv2.dispatch_workspace_bytes(T, K, E), dtype=torch.uint8, device=DEV))
+
+    b = bufs()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fcv2.dispatch_quant(x, ids, E, bits, group, flags, **b)  # warm-up outside the capture
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fcv2.dispatch_quant(x, ids, E, bits, group, flags, **b)
+    torch.cuda.synchronize()
+    for trial in range(3):
+        xh = W.tensor(3, 8 + trial, rows=T, cols=H)
+        idh = W.topk_routing(W.seed_for(3) + 10 + trial, T, E, K)
+        idh[trial, 0] = -1
+        x.copy_(to_dev_bf16(xh).view(T, H))
+        ids.copy_(torch.from_numpy(idh))
+        b["send_buf"].fill_(0xEE)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        e = bufs()
+        fcv2.dispatch_quant(x, ids, E, bits, group, flags, **e)  # eager, between the replays
+        torch.cuda.synchronize()
+        want, offs, src = O.dispatch_quant(xh, idh, E, bits, group, flags)
+        R = int(offs[E])
+        assert np.array_equal(b["expert_offsets"].cpu().numpy(), offs), f"replay {trial}: offsets"
+        assert np.array_equal(b["row_src"].cpu().numpy()[:R], src), f"replay {trial}: row_src"
+        assert np.array_equal(b["send_buf"].cpu().numpy()[:R], want), f"replay {trial}: rows differ from the oracle"
+        assert torch.equal(b["send_buf"][:R], e["send_buf"][:R]), f"replay {trial}: rows differ from the eager call"
