@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0
 LLC_BYTES = 256 << 20
 ALU_PEAK_TLOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # 39.3 T lane-operations/s: VALU issue without packed fp32
 # Measured with rocprofv3 counters at the headline shape (profiles/headline_step_b3_g128_n8.md); per launch.
-TRAFFIC_BYTES = {"quantize_pack": 41.29e6, "reduce_requant": 74.87e6, "unpack_dequant": 41.21e6}
+TRAFFIC_BYTES = {"quantize_pack": 41.29e6, "reduce_requant": 68.57e6, "unpack_dequant": 41.21e6}
 VALU_OPS_PER_ELEMENT = {"quantize_pack": 17.5, "reduce_requant": 62.8, "unpack_dequant": 6.6}
 
 

@@ -81,6 +81,16 @@ __device__ __forceinline__ void store_stream(void* p, uint16_t v) { __builtin_no
 __device__ __forceinline__ void store_stream(void* p, uint8_t v) { __builtin_nontemporal_store(v, reinterpret_cast<uint8_t*>(p)); }
 __device__ __forceinline__ void store_stream(void* p, float v) { __builtin_nontemporal_store(v, reinterpret_cast<float*>(p)); }
 
+// ---- block id -> tiles, per XCD -----------------------------------------------------------------------------------
+// The hardware deals workgroups to the 8 XCDs round-robin by id, and every XCD has an L2 of its own.  Blocks that work
+// on neighbouring tiles share cache lines of the metadata sections (a block's 32 groups are half a line of scales), so
+// each XCD takes one contiguous eighth of the tiles: a shared line is then fetched into one L2, not two.  The grid is
+// padded to a multiple of 8; ids past the last tile do nothing.
+constexpr uint32_t kXcds = 8;
+__device__ __forceinline__ uint32_t xcd_tile_block(uint32_t block_id, uint32_t padded_grid) {
+    return (block_id % kXcds) * (padded_grid / kXcds) + block_id / kXcds;
+}
+
 // ---- cross-lane helpers -------------------------------------------------------------------------------------
 template <int CTRL> __device__ __forceinline__ uint32_t dpp(uint32_t v) {
     // old = identity of the unsigned minimum: the move folds into v_min_u32_dpp

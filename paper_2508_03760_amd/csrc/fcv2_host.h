@@ -47,6 +47,8 @@ template <template <int, int, bool> class F, typename... A> static int by_format
 static inline int launch_status() { return hipGetLastError() == hipSuccess ? FCV2_OK : FCV2_ERR_LAUNCH; }
 
 static inline unsigned grid_lanes(uint32_t n_lanes) { return (unsigned)((n_lanes + kBlock - 1) / kBlock); }
+// the same padded to a multiple of the 8 XCDs, for kernels that map block ids with xcd_tile_block
+static inline unsigned grid_lanes_xcd(uint32_t n_lanes) { return (grid_lanes(n_lanes) + 7u) & ~7u; }
 
 constexpr int kChunk = 256;  // routed slots per block in the dispatch planning kernels
 

@@ -91,7 +91,7 @@ void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
     __shared__ uint4 lds[kBlock * ROW];
     __shared__ float tabs[kScaleTables];
     if (meta_mode_in == kMetaInt || meta_mode_out == kMetaInt) fill_scale_tables(tabs);
-    const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t L = xcd_tile_block(blockIdx.x, gridDim.x) * kBlock + threadIdx.x;
     if (L >= n_lanes) return;
     const uint32_t lig = threadIdx.x & (LPG - 1);
     uint4* row = &lds[threadIdx.x * ROW];
@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
     __shared__ uint4 lds[kBlock * ROW];
     __shared__ float tabs[kScaleTables];
     if (meta_mode_in == kMetaInt || meta_mode_out == kMetaInt) fill_scale_tables(tabs);
-    const uint32_t L = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t L = xcd_tile_block(blockIdx.x, gridDim.x) * kBlock + threadIdx.x;
     if (L >= n_lanes) return;
     const uint32_t lig = threadIdx.x & (LPG - 1);
     uint4* row = &lds[threadIdx.x * ROW];
@@ -221,7 +221,7 @@ template <int BITS, int G, bool SR> struct LaunchReduce {
                    float* sum_out, uint32_t mf_in, uint32_t mf_out, hipStream_t st) {
         constexpr int EPL = 16;  // 32 was measured: 180 VGPRs, two waves per SIMD, 15 % slower; 8 doubles the per-lane work
         const uint32_t n_lanes = (uint32_t)(n / EPL);
-        hipLaunchKernelGGL((k_reduce_requant<BITS, EPL, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st, peers,
+        hipLaunchKernelGGL((k_reduce_requant<BITS, EPL, G / EPL, SR>), dim3(grid_lanes_xcd(n_lanes)), dim3(kBlock), 0, st, peers,
                            n_peers, n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
         return launch_status();
     }
@@ -231,7 +231,7 @@ template <int BITS, int G, bool SR> struct LaunchReduceMixed {  // BITS = output
                    const Rec& rec_out, float* sum_out, uint32_t mf_in, uint32_t mf_out, hipStream_t st) {
         constexpr int EPL = 16;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
-        hipLaunchKernelGGL((k_reduce_requant_mixed<BITS, EPL, G / EPL, SR>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
+        hipLaunchKernelGGL((k_reduce_requant_mixed<BITS, EPL, G / EPL, SR>), dim3(grid_lanes_xcd(n_lanes)), dim3(kBlock), 0, st,
                            peers, n_peers, bits_in, n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
         return launch_status();
     }
