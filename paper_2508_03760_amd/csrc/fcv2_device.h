@@ -326,7 +326,6 @@ __device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint
 // Store the planes of this lane's EPL codes.  L = lane index inside the record (element index / EPL).
 // Plane stores: every store instruction of a wave covers consecutive bytes, and the record is on its way out of this
 // GPU, so they carry the non-temporal hint.
-#define ST(at, T, v) store_stream(at, (T)v)
 template <int BITS, int EPL> __device__ __forceinline__ void store_planes(uint8_t* base, const Rec& r, uint32_t L,
                                                                            const uint32_t (&c)[EPL / 4]) {
     using P = Planes<BITS>;
@@ -336,9 +335,9 @@ template <int BITS, int EPL> __device__ __forceinline__ void store_planes(uint8_
         for (int u = 0; u < U; u += 2) {
             uint8_t* at = base + (r.plane8 + (uint32_t)EPL * L + 8u * u);
             if (U >= 2)
-                ST(at, uint4, (make_uint4(c[2 * u], c[2 * u + 1], c[2 * u + 2], c[2 * u + 3])));
+                store_stream(at, make_uint4(c[2 * u], c[2 * u + 1], c[2 * u + 2], c[2 * u + 3]));
             else
-                ST(at, uint2, (make_uint2(c[0], c[1])));
+                store_stream(at, make_uint2(c[0], c[1]));
         }
     }
     if (P::w4) {
@@ -346,31 +345,29 @@ template <int BITS, int EPL> __device__ __forceinline__ void store_planes(uint8_
 #pragma unroll
         for (int u = 0; u < U; ++u) q[u] = pack_plane4<P::sh4, BITS>(c[2 * u], c[2 * u + 1]);
         uint8_t* at = base + (r.plane4 + (uint32_t)(EPL / 2) * L);
-        if (U == 4) ST(at, uint4, (make_uint4(q[0], q[1], q[2], q[3])));
-        if (U == 2) ST(at, uint2, (make_uint2(q[0], q[1])));
-        if (U == 1) ST(at, uint32_t, (q[0]));
+        if (U == 4) store_stream(at, make_uint4(q[0], q[1], q[2], q[3]));
+        if (U == 2) store_stream(at, make_uint2(q[0], q[1]));
+        if (U == 1) store_stream(at, q[0]);
     }
     if (P::w2) {
         uint32_t q[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) q[u] = pack_plane2<P::sh2, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFFFu;
         uint8_t* at = base + (r.plane2 + (uint32_t)(EPL / 4) * L);
-        if (U == 4) ST(at, uint2, (make_uint2(q[0] | (q[1] << 16), q[2] | (q[3] << 16))));
-        if (U == 2) ST(at, uint32_t, (q[0] | (q[1] << 16)));
-        if (U == 1) ST(at, uint16_t, ((uint16_t)q[0]));
+        if (U == 4) store_stream(at, make_uint2(q[0] | (q[1] << 16), q[2] | (q[3] << 16)));
+        if (U == 2) store_stream(at, q[0] | (q[1] << 16));
+        if (U == 1) store_stream(at, (uint16_t)q[0]);
     }
     if (P::w1) {
         uint32_t q = 0;
 #pragma unroll
         for (int u = 0; u < U; ++u) q |= (pack_plane1<P::sh1, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFu) << (8 * u);
         uint8_t* at = base + (r.plane1 + (uint32_t)(EPL / 8) * L);
-        if (U == 4) ST(at, uint32_t, (q));
-        if (U == 2) ST(at, uint16_t, ((uint16_t)q));
-        if (U == 1) ST(at, uint8_t, ((uint8_t)q));
+        if (U == 4) store_stream(at, q);
+        if (U == 2) store_stream(at, (uint16_t)q);
+        if (U == 1) store_stream(at, (uint8_t)q);
     }
 }
-
-#undef ST
 
 template <bool SR> __device__ __forceinline__ void store_meta(uint8_t* base, const Rec& r, uint32_t g, const GroupMeta& m, uint32_t mode) {
     if (mode == kMetaInt) {
