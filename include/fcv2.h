@@ -12,7 +12,10 @@
  * General rules for every call below
  *   - extern "C"; returns an FCV2_* status; never throws, never aborts, never synchronizes.
  *   - Pointers named *_dev are DEVICE pointers (HBM of the current HIP device); everything else is host memory.
- *   - The caller owns every buffer.  The library allocates no device memory and keeps no state between calls.
+ *   - The caller owns every buffer.  The library allocates no device memory and keeps no state between calls (no
+ *     caches, no environment variables): a call depends on its arguments and on the current HIP device only.
+ *   - FCV2_ERR_LAUNCH reports the status the runtime returned for this call's own launch; the runtime's "last error"
+ *     slot is neither read nor cleared, so an error left there by other code of the process is not mistaken for ours.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the default stream); results are
  *     valid once the caller has synchronized that stream.
  *   - Device pointers must be 16-byte aligned (FCV2_ERR_ALIGN otherwise).
@@ -32,9 +35,13 @@
  *   With FCV2_F_META_INT (Section 3.3, Eq. 1 and the second row of Table 4) scale and zero take one byte each:
  *   scale[g] is the signed byte scale_int = round(log2(scale) * 10), clamped to [-128, 127], and stands for the
  *   scale 2^(scale_int / 10) rounded to fp32; zero[g] is the unsigned zero-point round(-lo / scale) of the range
- *   widened to contain 0 and stands for the offset -(zero * scale); element = fma(code, scale, offset).  Meant for
- *   the low widths (at 7 and 8 bits the 2^(1/20) granularity of the scale costs several dB).  FCV2_F_META_FP32 and
- *   FCV2_F_META_INT exclude each other.
+ *   widened to contain 0 and stands for the offset -(zero * scale); element = fma(code, scale, offset).
+ *   Error bound with FCV2_F_META_INT: Eq. 1 rounds log2(scale) to the NEAREST tenth, so the decoded scale can be up to
+ *   2^(1/20) (3.5 %) below the exact one; codes are clamped to [0, qmax], and a value at the top of the range is then off
+ *   by up to (1/2 + 0.036 * qmax) steps instead of 1/2 (under 1 step up to 4 bits, about 9.7 steps at 8 bits); ranges
+ *   wider than qmax * 2^12.7 or narrower than qmax * 2^-12.8 clip at the ends of the byte.  The mode is the paper's
+ *   default for the low widths (Section 4.1: INT2 to INT4) and is accepted at every width for completeness.
+ *   FCV2_F_META_FP32 and FCV2_F_META_INT exclude each other.
  */
 #ifndef FCV2_H
 #define FCV2_H
@@ -116,7 +123,8 @@ int fcv2_unpack_dequant_slices(const void* const* records_dev, uint32_t n_slices
 int fcv2_reduce_requant(const void* const* peers_dev, int n_peers, uint64_t n, const fcv2_fmt_t* fmt_in,
                         const fcv2_fmt_t* fmt_out, void* packed_out_dev, float* sum_out_dev, void* hip_stream);
 
-/* MoE dispatch (Section 3.1: only the dispatch volume is quantized; Section 4.4): quantize every token once
+/* MoE dispatch (Section 3.1: only the dispatch volume is quantized; Section 4.4 measures it as an equal-split All2All;
+ * grouping the routed copies per expert is what a real dispatch needs on top): quantize every token once
  * and write one packed row per routed copy into per-expert contiguous send buffers.
  *   x_bf16_dev    [T, H] bf16, H % group == 0
  *   topk_ids_dev  [T, K] int32, expert id in [0, E) or -1 for a dropped slot
@@ -127,18 +135,17 @@ int fcv2_reduce_requant(const void* const* peers_dev, int n_peers, uint64_t n, c
  *   row_src_dev   [T*K] int32 out: entry r < R is t*K+k of the copy stored in row r; inside an expert rows are
  *                 in ascending t*K+k (a stable counting sort)
  *   workspace_dev at least fcv2_dispatch_workspace_bytes(T, K, E) bytes of scratch, 16-byte aligned
- * Ids outside [-1, E) are treated as dropped.  Limits (FCV2_ERR_UNSUPPORTED beyond): E <= 2048, T*K < 2^24,
+ * Ids outside [-1, E) are treated as dropped: the call is asynchronous and cannot report what only the device sees
+ * without a round trip to the host.  fcv2_dispatch_workspace_bytes gives the scratch size for a routing shape (counting
+ * sort of T*K slots into E experts: per-chunk histograms, expert totals, one destination row per slot).  Limits (FCV2_ERR_UNSUPPORTED beyond): E <= 2048, T*K < 2^24,
  * T*K*row_bytes < 2^32 (a send buffer below 4 GiB). */
 int fcv2_dispatch_workspace_bytes(uint32_t T, uint32_t K, uint32_t E, size_t* out);
 int fcv2_dispatch_quant(const void* x_bf16_dev, const int32_t* topk_ids_dev, uint32_t T, uint32_t H, uint32_t K,
                         uint32_t E, const fcv2_fmt_t* fmt, void* send_buf_dev, int32_t* expert_offsets_dev,
                         int32_t* row_src_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream);
 
-/* Diagnostic, not part of the codec: a plain streaming copy of `bytes` (a multiple of 16) from src_dev to
- * dst_dev, 16 bytes per lane, stores with the non-temporal hint.  The benchmark uses it to measure the practical
- * HBM ceiling next to the codec kernels and to calibrate memory-traffic counters against a transfer of known size. */
-int fcv2_stream_copy(const void* src_dev, void* dst_dev, uint64_t bytes, void* hip_stream);
-
+/* Text for a status code (static storage, never NULL), and the version of this interface (major * 100 + minor).
+ * House-keeping of the C ABI; they stand for nothing in the paper. */
 const char* fcv2_status_string(int status);
 int fcv2_version(void);
 

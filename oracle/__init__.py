@@ -4,6 +4,7 @@ TEST INFRASTRUCTURE ONLY.  Imported by tests/, by __graft_entry__.smoke() and by
 bench.py; never by the product package.  Works on numpy arrays; bf16 tensors travel as uint16 bit patterns.
 """
 import ctypes as C
+import os
 from dataclasses import dataclass
 
 import numpy as np
@@ -49,7 +50,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(_build.build())
+        # FCV2_ORACLE_SANITIZE=1: the build with AddressSanitizer and UndefinedBehaviorSanitizer (the process must have
+        # been started with the sanitizer runtime preloaded; tests/test_sanitizers.py does that in a child process)
+        L = C.CDLL(_build.build(sanitize=os.environ.get("FCV2_ORACLE_SANITIZE") == "1"))
         u8p, u16p, f32p, i32p = (C.POINTER(t) for t in (C.c_uint8, C.c_uint16, C.c_float, C.c_int32))
         fmtp = C.POINTER(_Fmt)
         L.orc_get_layout.argtypes = [C.c_uint64, fmtp, C.c_uint32, C.POINTER(_Layout)]

@@ -1,4 +1,5 @@
 """Compile libfcv2 (HIP kernels + C ABI) for gfx950 into paper_2508_03760_amd/libfcv2.so."""
+import hashlib
 import os
 import subprocess
 import sys
@@ -17,6 +18,27 @@ FLAGS = [
 
 def lib_path() -> str:
     return LIB
+
+
+def source_digest() -> str:
+    """Digest of everything the library is compiled from (sources, headers, flags)."""
+    h = hashlib.sha256(" ".join(FLAGS).encode())
+    inc = os.path.join(os.path.dirname(HERE), "include")
+    files = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith((".hip", ".h"))]
+    files += [os.path.join(inc, f) for f in sorted(os.listdir(inc)) if f.endswith(".h")]
+    for f in files:
+        h.update(os.path.basename(f).encode())
+        h.update(open(f, "rb").read())
+    return h.hexdigest()
+
+
+def is_current() -> bool:
+    """True if a built library is there and was built from the sources as they are now (the digest written next to it
+    at build time matches).  Content, not time stamps: a copy of the tree to another machine keeps the answer."""
+    try:
+        return os.path.exists(LIB) and open(LIB + ".srchash").read().strip() == source_digest()
+    except OSError:
+        return False
 
 
 def build(verbose: bool = False) -> str:
@@ -41,6 +63,8 @@ def build(verbose: bool = False) -> str:
         print(" ".join(link), flush=True)
     subprocess.run(link, check=True, cwd=CSRC)
     os.replace(LIB + ".tmp", LIB)
+    with open(LIB + ".srchash", "w") as f:
+        f.write(source_digest() + "\n")
     return LIB
 
 

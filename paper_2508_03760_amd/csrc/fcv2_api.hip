@@ -196,9 +196,8 @@ int fcv2_stream_copy(const void* src, void* dst, uint64_t bytes, void* stream) {
     if (!src || !dst || bytes == 0 || bytes % 16 != 0) return FCV2_ERR_INVALID_ARG;
     if (!aligned16(src) || !aligned16(dst)) return FCV2_ERR_ALIGN;
     const uint64_t n16 = bytes / 16;
-    hipLaunchKernelGGL(k_stream_copy, dim3((unsigned)((n16 + kBlock - 1) / kBlock)), dim3(kBlock), 0, (hipStream_t)stream,
-                       (const uint4*)src, (uint4*)dst, n16);
-    return launch_status();
+    return launch(k_stream_copy, dim3((unsigned)((n16 + kBlock - 1) / kBlock)), dim3(kBlock), 0, (hipStream_t)stream,
+                  (const uint4*)src, (uint4*)dst, n16);
 }
 
 }  // extern "C"

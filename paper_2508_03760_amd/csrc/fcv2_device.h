@@ -24,6 +24,7 @@
 #include <type_traits>
 
 #include "../../include/fcv2.h"
+#include "../../include/fcv2_diag.h"
 #include "fcv2_bits.h"
 
 namespace fcv2 {

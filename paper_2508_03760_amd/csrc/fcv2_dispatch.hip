@@ -314,21 +314,17 @@ template <int BITS, int G, bool SR> struct LaunchDispatch {
         if (plan.rows) {
             const dim3 grid((T + plan.rows - 1) / plan.rows), block(plan.threads);
             if (im)
-                hipLaunchKernelGGL((k_dispatch_rows_t<BITS, LPG, SR, true>), grid, block, plan.lds_bytes, st, (const uint4*)x, T, lpr, K,
-                                   dest, send, rec, row_bytes, meta_mode, plan.rows);
-            else
-                hipLaunchKernelGGL((k_dispatch_rows_t<BITS, LPG, SR, false>), grid, block, plan.lds_bytes, st, (const uint4*)x, T, lpr, K,
-                                   dest, send, rec, row_bytes, meta_mode, plan.rows);
-        } else {
-            const dim3 grid(grid_lanes(n_lanes)), block(kBlock);
-            if (im)
-                hipLaunchKernelGGL((k_dispatch_quant_t<BITS, LPG, SR, true>), grid, block, 0, st, (const uint4*)x, n_lanes, lpr, K, dest,
-                                   send, rec, row_bytes, meta_mode);
-            else
-                hipLaunchKernelGGL((k_dispatch_quant_t<BITS, LPG, SR, false>), grid, block, 0, st, (const uint4*)x, n_lanes, lpr, K, dest,
-                                   send, rec, row_bytes, meta_mode);
+                return launch(k_dispatch_rows_t<BITS, LPG, SR, true>, grid, block, plan.lds_bytes, st, (const uint4*)x, T, lpr, K, dest,
+                              send, rec, row_bytes, meta_mode, plan.rows);
+            return launch(k_dispatch_rows_t<BITS, LPG, SR, false>, grid, block, plan.lds_bytes, st, (const uint4*)x, T, lpr, K, dest, send,
+                          rec, row_bytes, meta_mode, plan.rows);
         }
-        return launch_status();
+        const dim3 grid(grid_lanes(n_lanes)), block(kBlock);
+        if (im)
+            return launch(k_dispatch_quant_t<BITS, LPG, SR, true>, grid, block, 0, st, (const uint4*)x, n_lanes, lpr, K, dest, send, rec,
+                          row_bytes, meta_mode);
+        return launch(k_dispatch_quant_t<BITS, LPG, SR, false>, grid, block, 0, st, (const uint4*)x, n_lanes, lpr, K, dest, send, rec,
+                      row_bytes, meta_mode);
     }
 };
 
@@ -340,11 +336,11 @@ int launch_dispatch(const fcv2_fmt_t* fmt, const void* x, const int32_t* ids, ui
     int32_t* hist = (int32_t*)((uint8_t*)ws + w.off_hist);
     int32_t* totals = (int32_t*)((uint8_t*)ws + w.off_totals);
     int32_t* dest = (int32_t*)((uint8_t*)ws + w.off_dest);
-    hipLaunchKernelGGL(k_dispatch_count, dim3(w.n_chunks), dim3(kChunk), E * 4, st, ids, w.n_slots, E, hist);
-    hipLaunchKernelGGL(k_dispatch_scan_chunks, dim3(E), dim3(256), 0, st, hist, w.n_chunks, E, totals);
-    hipLaunchKernelGGL(k_dispatch_rank, dim3(w.n_chunks), dim3(kChunk), (kChunk / 64 + 1) * E * 4, st, ids, w.n_slots, E, hist,
-                       (const int32_t*)totals, expert_offsets, dest, row_src);
-    if (launch_status() != FCV2_OK) return FCV2_ERR_LAUNCH;
+    if (launch(k_dispatch_count, dim3(w.n_chunks), dim3(kChunk), E * 4, st, ids, w.n_slots, E, hist) != FCV2_OK) return FCV2_ERR_LAUNCH;
+    if (launch(k_dispatch_scan_chunks, dim3(E), dim3(256), 0, st, hist, w.n_chunks, E, totals) != FCV2_OK) return FCV2_ERR_LAUNCH;
+    if (launch(k_dispatch_rank, dim3(w.n_chunks), dim3(kChunk), (kChunk / 64 + 1) * E * 4, st, ids, w.n_slots, E, (const int32_t*)hist,
+               (const int32_t*)totals, expert_offsets, dest, row_src) != FCV2_OK)
+        return FCV2_ERR_LAUNCH;
     return by_format<LaunchDispatch>(fmt, x, T, H, K, (const int32_t*)dest, send, rec, row_bytes, meta_mode_of(fmt), st);
 }
 

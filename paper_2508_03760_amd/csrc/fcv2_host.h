@@ -3,7 +3,9 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <stdlib.h>
+
+#include <tuple>
+#include <utility>
 
 #include "fcv2_device.h"
 
@@ -44,7 +46,18 @@ template <template <int, int, bool> class F, typename... A> static int by_format
     return FCV2_ERR_UNSUPPORTED;
 }
 
-static inline int launch_status() { return hipGetLastError() == hipSuccess ? FCV2_OK : FCV2_ERR_LAUNCH; }
+// Enqueues `kernel` and returns the status of THIS launch.  The arguments are converted to the kernel's own parameter
+// types and handed to hipLaunchKernel, whose return value is the launch's own: the runtime's "last error" slot, which
+// other code of the process may have set and may still want to read, is neither consulted nor cleared.
+template <typename... KArgs, typename... Args>
+static inline int launch(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t st, Args&&... args) {
+    static_assert(sizeof...(KArgs) == sizeof...(Args), "argument count differs from the kernel's parameter count");
+    std::tuple<KArgs...> vals{static_cast<KArgs>(std::forward<Args>(args))...};
+    void* ptrs[sizeof...(KArgs)];
+    std::apply([&](auto&... v) { size_t i = 0; ((ptrs[i++] = (void*)&v), ...); }, vals);
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, lds_bytes, st) == hipSuccess ? FCV2_OK
+                                                                                                                   : FCV2_ERR_LAUNCH;
+}
 
 static inline unsigned grid_lanes(uint32_t n_lanes) { return (unsigned)((n_lanes + kBlock - 1) / kBlock); }
 // the same padded to a multiple of the 8 XCDs, for kernels that map block ids with xcd_tile_block

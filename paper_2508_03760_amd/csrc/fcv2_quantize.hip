@@ -65,17 +65,14 @@ __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restr
 // Number of blocks of a persistent launch.  A compute unit holds 8 blocks of the quantize kernel (64 registers per
 // lane, 20 KiB of LDS per block).  A tensor of at most that many tiles gets one wave per tile, all resident at once;
 // a larger one gets 4 blocks per compute unit, each wave walking several tiles with the next loads in flight.
-// FCV2_BLOCKS_PER_CU overrides the choice (for experiments).
+// The compute-unit count is asked of the current device at every call (a cheap attribute read): nothing is cached, so a
+// process that moves between devices, or calls from several threads, always gets the count of the device it launches on.
 static unsigned persistent_grid(uint32_t n_tiles) {
-    static int cus = 0, forced = 0;
-    if (cus == 0) {
-        int dev = 0, n = 256;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 256;
-        if (const char* e = getenv("FCV2_BLOCKS_PER_CU")) forced = atoi(e) > 0 ? atoi(e) : 0;
-        cus = n > 0 ? n : 256;
-    }
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+        cus = 256;
     const unsigned need = (n_tiles + kWaves - 1) / kWaves;
-    const unsigned per_cu = forced ? (unsigned)forced : (need <= 8u * (unsigned)cus ? 8u : 4u);
+    const unsigned per_cu = need <= 8u * (unsigned)cus ? 8u : 4u;
     const unsigned blocks = per_cu * (unsigned)cus;
     return need < blocks ? need : blocks;
 }
@@ -87,12 +84,10 @@ template <int BITS, int G, bool SR> struct LaunchQuantize {
         const uint32_t n_lanes = (uint32_t)(n / EPL);
         const uint32_t n_tiles = (n_lanes + 63) / 64;
         if (meta_mode == kMetaInt)
-            hipLaunchKernelGGL((k_quantize_pack_t<BITS, G / EPL, SR, true>), dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
-                               (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_mode, n_lanes / n_slices, record_stride);
-        else
-            hipLaunchKernelGGL((k_quantize_pack_t<BITS, G / EPL, SR, false>), dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
-                               (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_mode, n_lanes / n_slices, record_stride);
-        return launch_status();
+            return launch(k_quantize_pack_t<BITS, G / EPL, SR, true>, dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
+                          (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_mode, n_lanes / n_slices, record_stride);
+        return launch(k_quantize_pack_t<BITS, G / EPL, SR, false>, dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
+                      (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_mode, n_lanes / n_slices, record_stride);
     }
 };
 int launch_quantize(const fcv2_fmt_t* fmt, const void* x, uint64_t n, void* out, const Rec& rec, uint32_t n_slices,

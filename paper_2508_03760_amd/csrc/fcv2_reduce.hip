@@ -221,9 +221,8 @@ template <int BITS, int G, bool SR> struct LaunchReduce {
                    float* sum_out, uint32_t mf_in, uint32_t mf_out, hipStream_t st) {
         constexpr int EPL = 16;  // 32 was measured: 180 VGPRs, two waves per SIMD, 15 % slower; 8 doubles the per-lane work
         const uint32_t n_lanes = (uint32_t)(n / EPL);
-        hipLaunchKernelGGL((k_reduce_requant<BITS, EPL, G / EPL, SR>), dim3(grid_lanes_xcd(n_lanes)), dim3(kBlock), 0, st, peers,
-                           n_peers, n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
-        return launch_status();
+        return launch(k_reduce_requant<BITS, EPL, G / EPL, SR>, dim3(grid_lanes_xcd(n_lanes)), dim3(kBlock), 0, st, peers, n_peers,
+                      n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
     }
 };
 template <int BITS, int G, bool SR> struct LaunchReduceMixed {  // BITS = output width
@@ -231,9 +230,8 @@ template <int BITS, int G, bool SR> struct LaunchReduceMixed {  // BITS = output
                    const Rec& rec_out, float* sum_out, uint32_t mf_in, uint32_t mf_out, hipStream_t st) {
         constexpr int EPL = 16;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
-        hipLaunchKernelGGL((k_reduce_requant_mixed<BITS, EPL, G / EPL, SR>), dim3(grid_lanes_xcd(n_lanes)), dim3(kBlock), 0, st,
-                           peers, n_peers, bits_in, n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
-        return launch_status();
+        return launch(k_reduce_requant_mixed<BITS, EPL, G / EPL, SR>, dim3(grid_lanes_xcd(n_lanes)), dim3(kBlock), 0, st, peers,
+                      n_peers, bits_in, n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
     }
 };
 int launch_reduce(const fcv2_fmt_t* fmt_in, const fcv2_fmt_t* fmt_out, const PeerPtrs& peers, int n_peers, uint64_t n,

@@ -83,12 +83,10 @@ template <int BITS, int G, bool SR> struct LaunchUnpack {
         constexpr int EPL = kEplStream;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
         if (out_fp32)
-            hipLaunchKernelGGL((k_unpack_dequant_t<BITS, G / EPL, SR, true>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
-                               records, n_lanes / n_slices, rec, n_lanes, (uint4*)out, meta_mode);
-        else
-            hipLaunchKernelGGL((k_unpack_dequant_t<BITS, G / EPL, SR, false>), dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st,
-                               records, n_lanes / n_slices, rec, n_lanes, (uint4*)out, meta_mode);
-        return launch_status();
+            return launch(k_unpack_dequant_t<BITS, G / EPL, SR, true>, dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st, records,
+                          n_lanes / n_slices, rec, n_lanes, (uint4*)out, meta_mode);
+        return launch(k_unpack_dequant_t<BITS, G / EPL, SR, false>, dim3(grid_lanes(n_lanes)), dim3(kBlock), 0, st, records,
+                      n_lanes / n_slices, rec, n_lanes, (uint4*)out, meta_mode);
     }
 };
 int launch_unpack(const fcv2_fmt_t* fmt, const PeerPtrs& records, uint32_t n_slices, const Rec& rec, uint64_t n, void* out,

@@ -55,11 +55,13 @@ _lib = None
 
 
 def lib():
-    """Load libfcv2.so (building it first only if no built library is there)."""
+    """Load libfcv2.so.  A built library that matches the sources is loaded as it is; a missing one, or one built from
+    other sources than the tree now holds (an edit since the last build), is compiled first.  A failing compile raises:
+    there is no other path."""
     global _lib
     if _lib is None:
         path = _build.lib_path()
-        if not os.path.exists(path):
+        if not os.path.exists(path) or not _build.is_current():
             _build.build()
         L = C.CDLL(path)
         fmtp, vp = C.POINTER(_Fmt), C.c_void_p
@@ -68,7 +70,7 @@ def lib():
         L.fcv2_unpack_dequant.argtypes = [vp, C.c_uint64, fmtp, vp, C.c_int, vp]
         L.fcv2_quantize_pack_slices.argtypes = [vp, C.c_uint64, C.c_uint32, fmtp, vp, C.c_uint64, vp]
         L.fcv2_unpack_dequant_slices.argtypes = [C.POINTER(vp), C.c_uint32, C.c_uint64, fmtp, vp, C.c_int, vp]
-        L.fcv2_stream_copy.argtypes = [vp, vp, C.c_uint64, vp]
+        L.fcv2_stream_copy.argtypes = [vp, vp, C.c_uint64, vp]  # include/fcv2_diag.h
         L.fcv2_reduce_requant.argtypes = [C.POINTER(vp), C.c_int, C.c_uint64, fmtp, fmtp, vp, vp, vp]
         L.fcv2_dispatch_workspace_bytes.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_size_t)]
         L.fcv2_dispatch_quant.argtypes = [vp, vp, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, fmtp, vp, vp, vp,

@@ -3,7 +3,7 @@
 // Build: g++ -std=c++17 -O2 -ffp-contract=off -fPIC -shared.
 #include <cstring>
 
-#include "fcv2_bits.h"
+#include "../../paper_2508_03760_amd/csrc/fcv2_bits.h"
 
 using namespace fcv2;
 

@@ -175,11 +175,13 @@ def test_random_shapes_and_formats():
         check_reduce(xs, bits, group, flags, f"random case {case}: reduce N={n_peers} n={n} b{bits} g{group} f{flags}")
 
 
-def test_maximum_tensor_size():
+@pytest.mark.parametrize("bits", [2, 8])
+def test_maximum_tensor_size(bits):
     """2^31 elements, the largest tensor a call takes (4 GiB of bf16): the 16M-element payload repeated 128 times on the
     GPU.  Groups are independent, so every 16M-element block of the packed record must equal the oracle's record of
-    the payload, section by section; the same for the decoded tensor.  Exercises the 32-bit offsets at their limit."""
-    bits, group, flags = 2, 128, SR
+    the payload, section by section; the same for the decoded tensor.  Exercises the 32-bit offsets at their limit: at
+    8 bits the byte plane alone is 2 GiB, so the metadata sections lie beyond offset 2^31."""
+    group, flags = 128, SR
     base = W.tensor(2, 0).reshape(-1)
     reps = (1 << 31) // base.size
     n = base.size * reps
@@ -189,7 +191,7 @@ def test_maximum_tensor_size():
     assert x.numel() == 1 << 31
     got = fcv2.quantize_pack(x, bits, group, flags)
     L = fcv2.get_layout(n, bits, group, flags)
-    assert L.total_bytes < 1 << 32
+    assert L.total_bytes < 1 << 32 and (bits != 8 or L.off_scale >= 1 << 31)
     want_d = torch.from_numpy(want).to(DEV)
     for name, off, size in sections(L, flags):
         per = size // reps
@@ -491,6 +493,30 @@ def test_dispatch_quant_send_buffer_off_the_line_grid():
         assert int(back[:base].max() if base else 0) == 0 and int(back[base + T * K * L.total_bytes:].max()) == 0, f"phase {phase}: wrote outside"
 
 
+def test_dispatch_quant_ids_outside_the_expert_range_are_dropped():
+    """An id outside [-1, E) cannot be reported by an asynchronous call without a device-to-host round trip; the
+    library documents that it treats such a slot as dropped.  So the result must be the reference result of the same
+    routing with those ids replaced by -1 (the reference itself refuses such ids and stays as it is)."""
+    T, H, K, E = 257, 512, 4, 24
+    x = W.tensor(3, 8, rows=T, cols=H)
+    ids = W.topk_routing(W.seed_for(3) + 9, T, E, K)
+    bad = ids.copy()
+    rng = np.random.default_rng(5)
+    for v in (E, E + 1, 2047, 2048, 1 << 20, 2**31 - 1, -2, -7, -(2**31)):
+        t, k = int(rng.integers(T)), int(rng.integers(K))
+        bad[t, k] = v
+    clean = np.where((bad < 0) | (bad >= E), -1, bad).astype(np.int32)
+    assert (clean != ids).sum() >= 5
+    with pytest.raises(ValueError):
+        O.dispatch_quant(x, bad, E, 2, 128, SR)  # the reference refuses them
+    send_o, offs_o, src_o = O.dispatch_quant(x, clean, E, 2, 128, SR)
+    send, offs, src = fcv2.dispatch_quant(to_dev_bf16(x).view(T, H), torch.from_numpy(bad).to(DEV), E, 2, 128, SR)
+    R = int(offs_o[E])
+    assert np.array_equal(offs.cpu().numpy(), offs_o)
+    assert np.array_equal(src.cpu().numpy()[:R], src_o)
+    assert np.array_equal(send.cpu().numpy()[:R], send_o)
+
+
 def test_dispatch_quant_degenerate_routing():
     T, H, K, E = 130, 512, 8, 256
     x = W.tensor(3, 1, rows=T, cols=H)
@@ -560,19 +586,11 @@ def test_workload3_full():
     check_dispatch(x, ids, w["experts"], 2, 128, SR, "workload 3")
 
 
-@pytest.mark.parametrize("bits,group", [(5, 64), (6, 256)])
+@pytest.mark.parametrize("bits,group", [(5, 64), (5, 256), (6, 64), (6, 256)])
 def test_workload4_full(bits, group):
     xs = [W.tensor(4, p).reshape(-1) for p in range(8)]
     check_codec(xs[0], bits, group, SR, f"workload 4 b{bits} g{group}")
     check_reduce(xs, bits, group, SR, f"workload 4 b{bits} g{group} N8")
-
-
-@pytest.mark.parametrize("bits,group", [(5, 256), (6, 64)])
-def test_workload4_other_formats_sampled(bits, group):
-    # the other two format pairs of workload 4, on a 1/16 slice of the rows
-    xs = [W.tensor(4, p, rows=512).reshape(-1) for p in range(8)]
-    check_codec(xs[0], bits, group, SR, f"workload 4 slice b{bits} g{group}")
-    check_reduce(xs, bits, group, SR, f"workload 4 slice b{bits} g{group} N8")
 
 
 @pytest.mark.parametrize("bits", [2, 3, 4])

@@ -4,9 +4,9 @@ No GPU and no compute calls: the C-ABI library is loaded only to check its expor
 fcv2_get_layout; the building blocks (csrc/fcv2_bits.h) are compiled for the host and held to the oracle.
 """
 import ctypes as C
+import importlib.util
 import os
 import re
-import subprocess
 
 import numpy as np
 import pytest
@@ -15,16 +15,18 @@ import oracle as O
 from paper_2508_03760_amd import build as B
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-CSRC = os.path.join(ROOT, "paper_2508_03760_amd", "csrc")
+
+
+def _hostcheck_build():
+    spec = importlib.util.spec_from_file_location("fcv2_hostcheck_build", os.path.join(ROOT, "tests", "hostcheck", "build.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    return mod
 
 
 @pytest.fixture(scope="module")
 def hc():
-    so = os.path.join(CSRC, "libfcv2_hostcheck.so")
-    src = os.path.join(CSRC, "fcv2_hostcheck.cpp")
-    newest = max(os.path.getmtime(src), os.path.getmtime(os.path.join(CSRC, "fcv2_bits.h")))
-    if not os.path.exists(so) or os.path.getmtime(so) < newest:
-        subprocess.run(["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fPIC", "-shared", "-o", so, src], check=True)
+    so = _hostcheck_build().build(sanitize=os.environ.get("FCV2_ORACLE_SANITIZE") == "1")
     L = C.CDLL(so)
     L.hc_div_mismatches.restype = C.c_uint64
     L.hc_div_mismatches.argtypes = [C.c_int, C.c_uint32, C.c_uint32]
@@ -53,11 +55,13 @@ def lib():
 
 
 def test_library_exports_every_declared_symbol(lib):
-    header = open(os.path.join(ROOT, "include", "fcv2.h")).read()
+    inc = os.path.join(ROOT, "include")
+    header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(fcv2_[a-z_0-9]+)\s*\(", header))
     assert names >= {"fcv2_get_layout", "fcv2_quantize_pack", "fcv2_unpack_dequant", "fcv2_reduce_requant",
-                     "fcv2_dispatch_workspace_bytes", "fcv2_dispatch_quant", "fcv2_status_string", "fcv2_version"}
+                     "fcv2_dispatch_workspace_bytes", "fcv2_dispatch_quant", "fcv2_status_string", "fcv2_version",
+                     "fcv2_quantize_pack_slices", "fcv2_unpack_dequant_slices", "fcv2_stream_copy"}
     for n in names:
         assert hasattr(lib, n), n
     lib.fcv2_status_string.restype = C.c_char_p

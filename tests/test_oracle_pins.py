@@ -371,6 +371,88 @@ def test_reduce_requant_different_output_format():
     assert np.array_equal(out, O.quantize_pack(W.f32_to_bf16_bits(s), *fout))
 
 
+def _spike_group(G, first, second):
+    """A group whose elements 0 and 1 are its two spikes (restored exactly on decode), the rest zeros."""
+    x = np.zeros(G, np.float32)
+    x[0], x[1] = first, second
+    return bf(x)
+
+
+def test_reduce_peer_order_is_sequential_from_peer_zero():
+    """Sections 3.1, 3.4: the local step adds the peers' chunks one after the other.  fp32 addition is not
+    associative, so the order is part of the result: with the decoded values 2^24, 1, -2^24 at one position
+    (spikes, hence exact) the chain ((2^24 + 1) + -2^24) loses the 1 to a tie-to-even rounding and gives 0,
+    every other order gives 1, and a sum carried in higher precision gives 1 as well."""
+    G, fmt = 32, (4, 32, SR)
+    big = float(2 ** 24)
+    A, B, C_ = _spike_group(G, big, -5.0), _spike_group(G, 1.0, -1.0), _spike_group(G, -big, 5.0)
+    pa, pb, pc = (O.quantize_pack(x, *fmt) for x in (A, B, C_))
+    for rec, x in ((pa, A), (pb, B), (pc, C_)):
+        assert np.array_equal(O.unpack_dequant(rec, G, *fmt)[:2], f32(x[:2]))  # the spikes decode exactly
+    s = lambda peers: O.reduce_requant(peers, G, fmt, want_sum=True)[1][0]
+    assert s([pa, pb, pc]) == 0.0
+    assert s([pc, pb, pa]) == 1.0 and s([pb, pc, pa]) == 1.0 and s([pa, pc, pb]) == 1.0
+    # four peers: sequential ((A + 1) + 1) + -A = 0; a pairwise tree (A + 1) + (1 + -A) would give 1, and a sum
+    # rounded only once would give 2
+    assert s([pa, pb, pb, pc]) == 0.0
+    # position 1 holds -5, -1, 5 (exact in every order): the neighbour is untouched
+    assert O.reduce_requant([pa, pb, pc], G, fmt, want_sum=True)[1][1] == -1.0
+
+
+def _round_fraction_to_f32(fr):
+    """Correctly rounded (nearest, ties to even) float32 of an exact rational, by integer arithmetic only."""
+    from fractions import Fraction
+    if fr == 0:
+        return np.float32(0.0)
+    sign, a = (-1, -fr) if fr < 0 else (1, fr)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1  # 2^e <= a < 2^(e+1)
+    e = max(e, -126)  # below the normal range the spacing stays 2^-149
+    q = a / Fraction(2) ** (e - 23)  # a in units of the last place
+    n, r = divmod(q.numerator, q.denominator)
+    twice = 2 * r
+    if twice > q.denominator or (twice == q.denominator and (n & 1)):
+        n += 1
+    return np.float32(sign * float(Fraction(n) * Fraction(2) ** (e - 23)))  # exact in float64, then exact in float32
+
+
+def test_decode_is_one_fused_multiply_add():
+    """Section 3.1 / 3.3: a value is reconstructed as code * scale + zero.  The oracle rounds that expression once
+    (a fused multiply-add): every decoded non-spike value equals the exact rational code * scale + zero rounded
+    to fp32 a single time.  Rounding the product first is a different function, and the data below tells them apart."""
+    from fractions import Fraction
+    rng = np.random.default_rng(31)
+    G, n = 32, 32 * 64
+    differs = 0
+    for bits in (4, 8):
+        for flags in (F32, SR | F32, SR):
+            x = bf(rng.standard_normal(n) * np.exp(rng.standard_normal(n)))
+            rec = O.quantize_pack(x, bits, G, flags)
+            L = O.get_layout(n, bits, G, flags)
+            codes = O.unpack_codes(rec, n, bits, G, flags)
+            v = O.unpack_dequant(rec, n, bits, G, flags)
+            m = 4 if flags & F32 else 2
+            raw_s = rec[L.off_scale:L.off_scale + m * L.n_groups]
+            raw_z = rec[L.off_zero:L.off_zero + m * L.n_groups]
+            sc = raw_s.view(np.float32) if flags & F32 else f32(raw_s.view(np.uint16))
+            zr = raw_z.view(np.float32) if flags & F32 else f32(raw_z.view(np.uint16))
+            spikes = set()
+            if flags & SR:
+                si = rec[L.off_spike_idx:L.off_spike_idx + 2 * L.n_groups]
+                spikes = {g * G + int(si[2 * g + k]) for g in range(L.n_groups) for k in (0, 1)}
+            for e in range(n):
+                if e in spikes:
+                    continue
+                g = e // G
+                q, s_, z_ = int(codes[e]), float(sc[g]), float(zr[g])
+                want = _round_fraction_to_f32(Fraction(q) * Fraction(s_) + Fraction(z_))
+                assert v[e] == want, (bits, flags, e, q, s_, z_)
+                two_step = np.float32(np.float32(np.float32(q) * np.float32(s_)) + np.float32(z_))
+                differs += int(two_step != want)
+    assert differs > 0  # the inputs do separate one rounding from two
+
+
 # ---- integer metadata (Section 3.3, Eq. 1, second row of Table 4) ---------------------------------------------
 
 def test_table4_footprint_with_integer_scales():
