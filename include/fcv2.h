@@ -59,7 +59,8 @@ enum {
     FCV2_ERR_UNSUPPORTED = -2, /* bits outside 2..8, group not 32/64/128/256, unknown flag, format pair not built */
     FCV2_ERR_ALIGN = -3,       /* a device pointer is not 16-byte aligned */
     FCV2_ERR_WORKSPACE = -4,   /* workspace smaller than fcv2_dispatch_workspace_bytes() */
-    FCV2_ERR_LAUNCH = -5       /* the HIP runtime refused the launch */
+    FCV2_ERR_LAUNCH = -5,      /* the HIP runtime refused the launch */
+    FCV2_ERR_SCRATCH = -6      /* the shape needs more than the static scratch of the no-allocation entry point */
 };
 
 enum { FCV2_F_SPIKE = 1u, FCV2_F_META_FP32 = 2u, FCV2_F_META_INT = 4u };
@@ -143,6 +144,23 @@ int fcv2_dispatch_workspace_bytes(uint32_t T, uint32_t K, uint32_t E, size_t* ou
 int fcv2_dispatch_quant(const void* x_bf16_dev, const int32_t* topk_ids_dev, uint32_t T, uint32_t H, uint32_t K,
                         uint32_t E, const fcv2_fmt_t* fmt, void* send_buf_dev, int32_t* expert_offsets_dev,
                         int32_t* row_src_dev, void* workspace_dev, size_t workspace_bytes, void* hip_stream);
+
+/* fcv2_dispatch_quant for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same results, same kernels as
+ * fcv2_dispatch_quant, but the planning scratch is a static device array inside the library (FCV2_STATIC_SCRATCH_BYTES
+ * per GPU the library runs on, held until the process ends) instead of workspace_dev.  The call itself allocates
+ * nothing and calls no allocating routine; the caller still passes the inputs and the three outputs.
+ *   - A routing shape with fcv2_dispatch_workspace_bytes(T, K, E) > FCV2_STATIC_SCRATCH_BYTES gives FCV2_ERR_SCRATCH
+ *     (2 MiB covers T*K = 131,072 routed slots over 256 experts, twice the DeepSeek-V3-shaped workload).
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU (different streams,
+ *     different threads) race on it and give wrong rows; calls on one stream, or ordered by events, are safe.  The
+ *     array keeps the last call's contents; no call depends on them.
+ *   - The first call on each device asks the runtime for the array's address (once per device; make that first call
+ *     outside a graph capture). */
+#define FCV2_STATIC_SCRATCH_BYTES (2u << 20)
+int fcv2_dispatch_quant_noalloc(const void* x_bf16_dev, const int32_t* topk_ids_dev, uint32_t T, uint32_t H, uint32_t K,
+                                uint32_t E, const fcv2_fmt_t* fmt, void* send_buf_dev, int32_t* expert_offsets_dev,
+                                int32_t* row_src_dev, void* hip_stream);
 
 /* Text for a status code (static storage, never NULL), and the version of this interface (major * 100 + minor).
  * House-keeping of the C ABI; they stand for nothing in the paper. */

@@ -35,6 +35,32 @@ static Rec rec_of(const fcv2_layout_t& l) {
 
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
+// Largest tensor the kernels index with 32-bit offsets: 2^31 elements (a 4 GiB bf16 tensor).
+static const uint64_t kMaxElems = 1ull << 31;
+
+// Argument checks and launch of the dispatch call; serves both entry points (workspace from the caller, or the
+// library's static scratch).
+int dispatch_checked(const void* x, const int32_t* ids, uint32_t T, uint32_t H, uint32_t K, uint32_t E, const fcv2_fmt_t* fmt, void* send,
+                     int32_t* expert_offsets, int32_t* row_src, void* ws, size_t ws_bytes, void* stream) {
+    if (!x || !ids || !fmt || !send || !expert_offsets || !row_src || !ws) return FCV2_ERR_INVALID_ARG;
+    size_t need = 0;
+    int rc = fcv2_dispatch_workspace_bytes(T, K, E, &need);
+    if (rc != FCV2_OK) return rc;
+    fcv2_layout_t l;
+    rc = fcv2_get_layout(H, fmt, FCV2_ROW_ALIGN, &l);
+    if (rc != FCV2_OK) return rc;
+    if ((uint64_t)T * H > kMaxElems) return FCV2_ERR_UNSUPPORTED;
+    // rows are addressed with 24-bit row numbers and 32-bit byte offsets inside the send buffer
+    if ((uint64_t)T * K >= (1u << 24) || l.total_bytes >= (1u << 24) || (uint64_t)T * K * l.total_bytes > 0xFFFFFFFFull)
+        return FCV2_ERR_UNSUPPORTED;
+    if (ws_bytes < need) return FCV2_ERR_WORKSPACE;
+    if (!aligned16(x) || !aligned16(send) || !aligned16(ws) || ((uintptr_t)ids & 3u) || ((uintptr_t)expert_offsets & 3u) ||
+        ((uintptr_t)row_src & 3u))
+        return FCV2_ERR_ALIGN;
+    return launch_dispatch(fmt, x, ids, T, H, K, E, (uint8_t*)send, expert_offsets, row_src, ws, rec_of(l), (uint32_t)l.total_bytes,
+                           (hipStream_t)stream);
+}
+
 }  // namespace fcv2
 
 using namespace fcv2;
@@ -51,6 +77,7 @@ const char* fcv2_status_string(int s) {
         case FCV2_ERR_ALIGN: return "device pointer not 16-byte aligned";
         case FCV2_ERR_WORKSPACE: return "workspace too small";
         case FCV2_ERR_LAUNCH: return "kernel launch failed";
+        case FCV2_ERR_SCRATCH: return "routing shape exceeds the static scratch of the no-allocation entry point";
     }
     return "unknown status";
 }
@@ -86,9 +113,6 @@ int fcv2_get_layout(uint64_t n, const fcv2_fmt_t* fmt, uint32_t align, fcv2_layo
     out->total_bytes = round_up(off, align);  // the next record starts aligned too
     return FCV2_OK;
 }
-
-// Largest tensor the kernels index with 32-bit offsets: 2^31 elements (a 4 GiB bf16 tensor).
-static const uint64_t kMaxElems = 1ull << 31;
 
 // Slices of a two-step AllReduce payload: equal length, whole groups, whole 2048-element wave tiles.
 static int check_slices(uint64_t n, uint32_t n_slices, const fcv2_fmt_t* fmt, fcv2_layout_t* slice_layout) {
@@ -173,23 +197,7 @@ int fcv2_dispatch_workspace_bytes(uint32_t T, uint32_t K, uint32_t E, size_t* ou
 
 int fcv2_dispatch_quant(const void* x, const int32_t* ids, uint32_t T, uint32_t H, uint32_t K, uint32_t E, const fcv2_fmt_t* fmt,
                         void* send, int32_t* expert_offsets, int32_t* row_src, void* ws, size_t ws_bytes, void* stream) {
-    if (!x || !ids || !fmt || !send || !expert_offsets || !row_src || !ws) return FCV2_ERR_INVALID_ARG;
-    size_t need = 0;
-    int rc = fcv2_dispatch_workspace_bytes(T, K, E, &need);
-    if (rc != FCV2_OK) return rc;
-    fcv2_layout_t l;
-    rc = fcv2_get_layout(H, fmt, FCV2_ROW_ALIGN, &l);
-    if (rc != FCV2_OK) return rc;
-    if ((uint64_t)T * H > kMaxElems) return FCV2_ERR_UNSUPPORTED;
-    // rows are addressed with 24-bit row numbers and 32-bit byte offsets inside the send buffer
-    if ((uint64_t)T * K >= (1u << 24) || l.total_bytes >= (1u << 24) || (uint64_t)T * K * l.total_bytes > 0xFFFFFFFFull)
-        return FCV2_ERR_UNSUPPORTED;
-    if (ws_bytes < need) return FCV2_ERR_WORKSPACE;
-    if (!aligned16(x) || !aligned16(send) || !aligned16(ws) || ((uintptr_t)ids & 3u) || ((uintptr_t)expert_offsets & 3u) ||
-        ((uintptr_t)row_src & 3u))
-        return FCV2_ERR_ALIGN;
-    return launch_dispatch(fmt, x, ids, T, H, K, E, (uint8_t*)send, expert_offsets, row_src, ws, rec_of(l), (uint32_t)l.total_bytes,
-                           (hipStream_t)stream);
+    return fcv2::dispatch_checked(x, ids, T, H, K, E, fmt, send, expert_offsets, row_src, ws, ws_bytes, stream);
 }
 
 int fcv2_stream_copy(const void* src, void* dst, uint64_t bytes, void* stream) {

@@ -1,4 +1,6 @@
 // fcv2_dispatch.hip -- fcv2_dispatch_quant: stable counting sort of the routed copies, then quantize-and-scatter (Sections 3.1, 4.4).
+#include <atomic>
+
 #include "fcv2_host.h"
 
 namespace fcv2 {
@@ -345,3 +347,43 @@ int launch_dispatch(const fcv2_fmt_t* fmt, const void* x, const int32_t* ids, ui
 }
 
 }  // namespace fcv2
+
+// ---- the dispatch call for callers that cannot allocate ------------------------------------------------------------
+// The planning kernels' scratch (per-chunk histograms, expert totals, one destination row per slot) lives in a
+// file-scope device array instead of a caller-supplied workspace.  Every GPU the library runs on holds its own copy of
+// the array, at its own address, until the process ends.  In host code the array's name is only a stand-in for the
+// device symbol: the address that kernels and copies need is asked of the runtime once per device
+// (hipGetSymbolAddress, with that device current) and kept; host code below uses that pointer, never the name.
+static __device__ __align__(256) uint8_t scratch[FCV2_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];  // zero-initialised; filled on the first call on each device
+
+// Address of `scratch` on the current device, or nullptr (the runtime refused, or a device ordinal beyond kMaxDevices).
+void* scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    // Two threads may both get here on a first call; both are told the same address, so the race is harmless.
+    void* q = nullptr;
+    if (hipGetSymbolAddress(&q, HIP_SYMBOL(scratch)) != hipSuccess || !q) return nullptr;
+    g_scratch_ptr[dev].store(q, std::memory_order_release);
+    return q;
+}
+}  // namespace
+
+extern "C" int fcv2_dispatch_quant_noalloc(const void* x, const int32_t* ids, uint32_t T, uint32_t H, uint32_t K, uint32_t E,
+                                           const fcv2_fmt_t* fmt, void* send, int32_t* expert_offsets, int32_t* row_src, void* stream) {
+    size_t need = 0;
+    const int rc = fcv2_dispatch_workspace_bytes(T, K, E, &need);
+    if (rc != FCV2_OK) return rc;
+    if (need > (size_t)FCV2_STATIC_SCRATCH_BYTES) return FCV2_ERR_SCRATCH;  // the routing shape does not fit the static array
+    void* ws = scratch_of_current_device();
+    if (!ws) return FCV2_ERR_LAUNCH;
+    // Nothing in the scratch has to start at zero: the counting kernel writes every histogram entry of every chunk, the
+    // scan every total, the rank kernel every destination slot, before any of them is read.
+    return fcv2::dispatch_checked(x, ids, T, H, K, E, fmt, send, expert_offsets, row_src, ws, FCV2_STATIC_SCRATCH_BYTES, stream);
+}
+

@@ -91,4 +91,8 @@ int launch_dispatch(const fcv2_fmt_t* fmt, const void* x, const int32_t* ids, ui
                     uint8_t* send, int32_t* expert_offsets, int32_t* row_src, void* ws, const Rec& rec, uint32_t row_bytes,
                     hipStream_t st);
 
+// The checked dispatch call behind both C entry points (defined with the C ABI).
+int dispatch_checked(const void* x, const int32_t* ids, uint32_t T, uint32_t H, uint32_t K, uint32_t E, const fcv2_fmt_t* fmt, void* send,
+                     int32_t* expert_offsets, int32_t* row_src, void* ws, size_t ws_bytes, void* stream);
+
 }  // namespace fcv2

@@ -20,6 +20,7 @@ ABSENT = 2**64 - 1
 TENSOR_ALIGN = 256
 ROW_ALIGN = 16
 MAX_PEERS = 16
+STATIC_SCRATCH_BYTES = 2 << 20
 
 
 class Fcv2Error(RuntimeError):
@@ -75,6 +76,7 @@ def lib():
         L.fcv2_dispatch_workspace_bytes.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.POINTER(C.c_size_t)]
         L.fcv2_dispatch_quant.argtypes = [vp, vp, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, fmtp, vp, vp, vp,
                                           vp, C.c_size_t, vp]
+        L.fcv2_dispatch_quant_noalloc.argtypes = [vp, vp, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, fmtp, vp, vp, vp, vp]
         L.fcv2_status_string.argtypes = [C.c_int]
         L.fcv2_status_string.restype = C.c_char_p
         L.fcv2_version.restype = C.c_int
@@ -235,4 +237,19 @@ def dispatch_quant(x: torch.Tensor, topk_ids: torch.Tensor, E, bits, group, flag
                                      C.byref(_Fmt(bits, group, flags)), _dev(send_buf, "send_buf"),
                                      _dev(expert_offsets, "expert_offsets"), _dev(row_src, "row_src"),
                                      _dev(workspace, "workspace"), workspace.numel(), _stream()), "fcv2_dispatch_quant")
+    return send_buf, expert_offsets, row_src
+
+
+def dispatch_quant_noalloc(x: torch.Tensor, topk_ids: torch.Tensor, E, bits, group, flags, send_buf: torch.Tensor,
+                           expert_offsets: torch.Tensor, row_src: torch.Tensor):
+    """fcv2_dispatch_quant_noalloc: as dispatch_quant, but the planning scratch is the library's static device array.
+    The caller passes every output; this binding allocates nothing either."""
+    T, H = x.shape
+    K = topk_ids.shape[1]
+    if x.dtype != torch.bfloat16 or topk_ids.dtype != torch.int32 or topk_ids.shape[0] != T:
+        raise Fcv2Error("x must be [T,H] bfloat16 and topk_ids [T,K] int32")
+    _check(lib().fcv2_dispatch_quant_noalloc(_dev(x, "x"), _dev(topk_ids, "topk_ids"), T, H, K, E,
+                                             C.byref(_Fmt(bits, group, flags)), _dev(send_buf, "send_buf"),
+                                             _dev(expert_offsets, "expert_offsets"), _dev(row_src, "row_src"), _stream()),
+           "fcv2_dispatch_quant_noalloc")
     return send_buf, expert_offsets, row_src
