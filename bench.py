@@ -1,17 +1,20 @@
 """Benchmark of libfcv2 on one MI355X.
 
-One "step" is one pass of the whole codec hot path over the Llama-3-8B-shaped AllReduce payload
-(bf16 [4096 x 4096], 3-bit = 2+1 split, group 128, spike reserving, 8 simulated peer chunks):
-    fcv2_quantize_pack(x)  ->  fcv2_reduce_requant(8 packed peer chunks)  ->  fcv2_unpack_dequant(result, bf16)
-i.e. the three kernels one rank runs locally in a two-step quantized AllReduce.  All inputs are resident in HBM
-before the timed region.  Buffer sets are rotated so that every step reads lines that are not in the 256 MB
-last-level cache (the whole working set of one step is smaller than that cache).  Before the warm-up the same step
-runs untimed for about 30 ms, so that the GPU is at its sustained clocks when the W warm-up steps and the K timed
-steps run; the figure is sustained throughput, not the first milliseconds after idling.
+One "step" is the pair of calls the metric names, on the Llama-3-8B-shaped AllReduce payload (bf16 [4096 x 4096],
+3-bit = 2+1 split, group 128, spike reserving, 8 simulated peer chunks):
+    fcv2_quantize_pack(x)  ->  fcv2_reduce_requant(8 packed peer chunks)
+`value` = algorithmic bytes of the two calls / time of a step (effective HBM GB/s).  The step with the third local call
+of a two-step quantized AllReduce added (fcv2_unpack_dequant of the result) is reported beside it as
+`three_call_step`.  All inputs are resident in HBM before the timed region.  Buffer sets are rotated so that every step
+reads lines that are not in the 256 MB last-level cache (the working set of one step is smaller than that cache).
+Before the warm-up the same step runs untimed for about 30 ms, so that the GPU is at its sustained clocks when the W
+warm-up steps and the K timed steps run; the figure is sustained throughput, not the first milliseconds after idling.
 
-Prints ONE JSON line.  `value` = algorithmic bytes of a step / time of a step (effective HBM GB/s).
-Extra keys: per-kernel figures, a sweep over bit widths 2..8, the dispatch workload, the roofline of the
-dominant kernel and the CPU oracle timed beside it.
+Prints ONE JSON line.  `roofline` is the dominant kernel (reduce_requant) against HBM: algorithmic bytes per launch
+divided by its launch duration, measured here with HIP events on the launch stream, over the 8 TB/s peak; `traffic` and
+the instruction counts of `alu_roofline` are read from the committed rocprofv3 summary under profiles/ (counters cannot
+be read inside this process).  Extra keys: per-kernel figures, a sweep over bit widths 2..8, the dispatch workload and
+the CPU oracle timed beside it.
 """
 import argparse
 import json
@@ -26,9 +29,20 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 LLC_BYTES = 256 << 20
 ALU_PEAK_TLOPS = 256 * 4 * 16 * 2.4e9 / 1e12  # 39.3 T lane-operations/s: VALU issue without packed fp32
-# Measured with rocprofv3 counters at the headline shape (profiles/headline_step_b3_g128_n8.md); per launch.
-TRAFFIC_BYTES = {"quantize_pack": 41.29e6, "reduce_requant": 68.57e6, "unpack_dequant": 41.21e6}
-VALU_OPS_PER_ELEMENT = {"quantize_pack": 17.5, "reduce_requant": 62.8, "unpack_dequant": 6.6}
+PROFILE = os.path.join(ROOT, "profiles", "headline_step_b3_g128_n8.md")
+
+
+def profile_counters(path=PROFILE):
+    """Per-kernel counter figures of the headline shape from the committed rocprofv3 summary: the line that starts with
+    `counters-json:` holds {kernel: {"hbm_bytes_per_launch": ..., "valu_per_element": ...}}.  None if the file or the
+    line is missing (the bench line then carries null for what it cannot know)."""
+    try:
+        for line in open(path):
+            if line.startswith("counters-json:"):
+                return json.loads(line[len("counters-json:"):])
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def packed_bytes(n, bits, group, spike=True, int_meta=False):
@@ -114,6 +128,7 @@ def main():
                 )
 
     KERNELS = ("quantize_pack", "reduce_requant", "unpack_dequant")
+    STEP = ("quantize_pack", "reduce_requant")  # the calls the metric names
 
     def timed(fn, count, warmup):
         """HIP events on the launch stream around `count` back-to-back calls; returns ms per call."""
@@ -134,13 +149,13 @@ def main():
         if rc != 0:
             raise RuntimeError(f"libfcv2 {name} failed: {rc}")
 
-    def run_steps(sets, bits, steps, warmup):
-        """ms per step: one step = the three calls of the hot path, on rotating buffer sets."""
+    def run_steps(sets, bits, steps, warmup, names=STEP):
+        """ms per step: one step = the calls `names` one after the other, on rotating buffer sets."""
         bind_calls(sets, bits)
 
         def step(i):
             s = sets[i % len(sets)]
-            for name in KERNELS:
+            for name in names:
                 call(s, name)
 
         return timed(step, steps, warmup)
@@ -159,35 +174,38 @@ def main():
     sets = make_sets(bits, n_sets_for(bits))
     # Bring the GPU to its sustained clocks first: after idling it needs some tens of milliseconds of work to get there
     # (measured: the first 100 steps after set-up run 8 % slower than steps 300 onwards).  Untimed, like the warm-up.
-    run_steps(sets, bits, 600, 0)
-    ms_step = run_steps(sets, bits, args.steps, args.warmup)  # the timed region proper
+    run_steps(sets, bits, 600, 0, KERNELS)
+    ms_step = run_steps(sets, bits, args.steps, args.warmup)  # the timed region proper: quantize_pack + reduce_requant
+    ms_step3 = run_steps(sets, bits, args.steps, args.warmup, KERNELS)  # with unpack_dequant: one rank's three local calls
     kern_ms = run_kernels(sets, bits, args.steps, 3)           # the same launches, one kernel at a time
     ab = algo_bytes(bits)
-    total_bytes = sum(ab.values())
+    total_bytes = sum(ab[k] for k in STEP)
+    total_bytes3 = sum(ab.values())
     value = total_bytes / (ms_step * 1e-3) / 1e9
     kernels = {k: dict(us=round(kern_ms[k] * 1e3, 2), algorithmic_bytes=ab[k],
                        gbs=round(ab[k] / (kern_ms[k] * 1e-3) / 1e9, 1),
                        frac_of_hbm_peak=round(ab[k] / (kern_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)) for k in ab}
     dom = "reduce_requant"
-    kname = f"k_reduce_requant<3, 16, 8, true> ({dom}, N={n_peers})"
-    traffic_source = "profiles/headline_step_b3_g128_n8.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, scaled by a copy of known size)"
-    # The dominant kernel against HBM, the bound the benchmark's metric is stated in ...
-    hbm_roofline = dict(bound="hbm", kernel=kname, achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=round(kernels[dom]["gbs"] / HBM_PEAK_GBS, 4), traffic=TRAFFIC_BYTES[dom], traffic_source=traffic_source)
-    # ... and against the bound that limits it: VALU issue (rocprofv3: the VALUs issue in 98 % of its cycles).
-    # achieved = algorithmic lane-operations per output element x elements / duration, where algorithmic = what the
-    # definition itself needs at N peers: per peer-element extract + FMA + add, per output element bf16 rounding (1/2),
-    # order key, two running top-2 selections (2 x 2), subtract, multiply, convert, pack.  executed = VALU instructions
-    # per output element as counted by rocprofv3 (SQ_INSTS_VALU): unpacking split planes, metadata, spike patching and
-    # cross-lane merges come on top of the algorithmic count.
-    algo_ops = 3.0 * n_peers + 9.5
-    ops_s = lambda per_elem: per_elem * n / (kern_ms[dom] * 1e-3) / 1e12
-    roofline = dict(bound="alu", kernel=kname, achieved=round(ops_s(algo_ops), 2), peak=round(ALU_PEAK_TLOPS, 2),
-                    unit="T lane-op/s", frac=round(ops_s(algo_ops) / ALU_PEAK_TLOPS, 4), traffic=TRAFFIC_BYTES[dom],
-                    traffic_source=traffic_source, algorithmic_ops_per_element=algo_ops,
-                    executed_ops_per_element=VALU_OPS_PER_ELEMENT[dom], executed=round(ops_s(VALU_OPS_PER_ELEMENT[dom]), 2),
-                    frac_executed=round(ops_s(VALU_OPS_PER_ELEMENT[dom]) / ALU_PEAK_TLOPS, 4),
-                    peak_note="256 CU x 4 SIMD x 16 lanes x 2.4 GHz, no packed fp32; traffic = HBM bytes per launch")
+    kname = f"k_reduce_requant ({dom}, 3 bits, G=128, N={n_peers})"
+    prof = profile_counters() or {}
+    pk = prof.get(dom, {})
+    traffic = pk.get("hbm_bytes_per_launch")
+    traffic_source = ("profiles/headline_step_b3_g128_n8.md (rocprofv3 FETCH_SIZE and WRITE_SIZE, each scaled by the same counter "
+                      "on a copy of known size)") if traffic is not None else None
+    # The dominant kernel against HBM, the bound the metric is stated in: algorithmic bytes per launch ((N + 1) x the
+    # packed record) / the launch duration measured above with HIP events / 8 TB/s.
+    roofline = dict(bound="hbm", kernel=kname, achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(kernels[dom]["gbs"] / HBM_PEAK_GBS, 4), traffic=traffic, traffic_source=traffic_source,
+                    algorithmic_bytes=ab[dom], us_per_launch=kernels[dom]["us"])
+    # What limits it in practice is VALU issue; the same launch against that bound, for context.  executed = VALU
+    # instructions per output element from the same rocprofv3 summary (SQ_INSTS_VALU); peak = 256 CU x 4 SIMD x 16 lanes x
+    # 2.4 GHz, no packed fp32.
+    alu_roofline = None
+    if pk.get("valu_per_element") is not None:
+        ops_s = pk["valu_per_element"] * n / (kern_ms[dom] * 1e-3) / 1e12
+        alu_roofline = dict(bound="alu", kernel=kname, achieved=round(ops_s, 2), peak=round(ALU_PEAK_TLOPS, 2), unit="T lane-op/s",
+                            frac=round(ops_s / ALU_PEAK_TLOPS, 4), executed_ops_per_element=pk["valu_per_element"],
+                            source="profiles/headline_step_b3_g128_n8.md (SQ_INSTS_VALU x 64 lanes / elements)")
     # practical streaming ceiling: the library's plain copy kernel on 1 GiB (source and destination together are eight
     # times the 256 MB last-level cache, so this is an HBM figure)
     import ctypes as C
@@ -207,6 +225,8 @@ def main():
     del csets
     # warm-cache figure for context: one buffer set, everything stays in the last-level cache
     ms_warm = run_steps(sets[:1], bits, args.steps, args.warmup)
+    three = dict(step="quantize_pack + reduce_requant + unpack_dequant", ms_per_step=round(ms_step3, 5), algorithmic_bytes=total_bytes3,
+                 gbs=round(total_bytes3 / (ms_step3 * 1e-3) / 1e9, 1), frac_of_hbm_peak=round(total_bytes3 / (ms_step3 * 1e-3) / 1e9 / HBM_PEAK_GBS, 4))
     del sets
     torch.cuda.empty_cache()
 
@@ -220,7 +240,7 @@ def main():
             abb = algo_bytes(b)
             sweep[str(b)] = {k: dict(us=round(k_b[k] * 1e3, 2), gbs=round(abb[k] / (k_b[k] * 1e-3) / 1e9, 1),
                                      frac=round(abb[k] / (k_b[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)) for k in abb}
-            sweep[str(b)]["step_gbs"] = round(sum(abb.values()) / (ms_b * 1e-3) / 1e9, 1)
+            sweep[str(b)]["step_gbs"] = round(sum(abb[k] for k in STEP) / (ms_b * 1e-3) / 1e9, 1)
             del s
             torch.cuda.empty_cache()
         w3 = W.WORKLOADS[3]
@@ -485,11 +505,10 @@ def main():
         t = time.perf_counter()
         for _ in range(reps):
             O.quantize_pack(xs_host[0], *fmt)
-            r = O.reduce_requant(peers_o, n, fmt)
-            O.unpack_dequant(r, n, *fmt, O.DT_BF16)
+            O.reduce_requant(peers_o, n, fmt)
         dt = (time.perf_counter() - t) / reps
         cpu = dict(value=round(total_bytes / dt / 1e9, 4), unit="GB/s", cores=1, kind="oracle",
-                   sample=f"{reps} full steps of the same workload (quantize_pack + reduce_requant N=8 + unpack_dequant "
+                   sample=f"{reps} full steps of the same workload (quantize_pack + reduce_requant N=8 "
                           f"on 4096x4096, 3-bit), {dt:.2f} s per step on one host thread")
         # the same oracle on all host cores: threads over disjoint row blocks (groups are independent; the calls
         # release the interpreter lock), each thread running the three calls on its block
@@ -503,8 +522,7 @@ def main():
 
         def block_step(j):
             O.quantize_pack(xb[j][0], *fmt)
-            rj = O.reduce_requant(pb[j], blk, fmt)
-            O.unpack_dequant(rj, blk, *fmt, O.DT_BF16)
+            O.reduce_requant(pb[j], blk, fmt)
 
         reps_mt = 8
         with ThreadPoolExecutor(n_thr) as pool:
@@ -522,12 +540,13 @@ def main():
         "ms_per_step": round(ms_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": W.WORKLOADS[2]["name"] + "_b3_g128_sr_N8", "elements": n, "bits": 3, "group": 128,
-                   "spike_reserving": True, "peers": n_peers, "step": "quantize_pack + reduce_requant + unpack_dequant",
+                   "spike_reserving": True, "peers": n_peers, "step": "quantize_pack + reduce_requant",
                    "buffer_sets_rotated": n_sets_for(3), "untimed_spin_up_steps": 600},
         "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
-        "warm_cache_gbs": round(total_bytes / (ms_warm * 1e-3) / 1e9, 1),
+        "warm_cache_gbs": round(total_bytes / (ms_warm * 1e-3) / 1e9, 1),  # the same two-call step on one buffer set
         "copy_ceiling_gbs": round(copy_gbs, 1), "copy_same_size_as_quantize_pack": copy_same_size,
-        "kernels": kernels, "roofline": roofline, "hbm_roofline": hbm_roofline, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
+        "three_call_step": three,
+        "kernels": kernels, "roofline": roofline, "alu_roofline": alu_roofline, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
         "quality_proxy_sqnr": quality, "low_bit_default_shape_g32": low_bit, "two_step_allreduce_rank_share": two_step, "micro_chunk_pipelining": pipelined, "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
     }
     print(json.dumps(out))

@@ -285,3 +285,28 @@ def test_dispatch_launch_plan(hc):
                     w = -(-r * lpr // 64)
                     assert (w * 64 - r * lpr) * 1024 // (w * 64) > idle
 
+
+
+def test_bench_reads_its_counters_from_the_committed_profile():
+    """bench.py takes `traffic` and the VALU counts of its roofline objects from the rocprofv3 summary under profiles/;
+    the machine-readable line it parses must say what the summary's counter table says."""
+    import bench
+    pc = bench.profile_counters()
+    assert pc and {"quantize_pack", "reduce_requant", "unpack_dequant"} <= set(pc)
+    text = open(bench.PROFILE).read()
+    text = text[text.index("## Counters, averages per launch"):]
+    text = text[:text.index("\n## ", 4)]
+    rows = {}
+    for line in text.splitlines():
+        m = re.match(r"\| fcv2::k_(quantize_pack|reduce_requant|unpack_dequant)\S*.*?\|(.*)\|\s*$", line)
+        cells = [c.strip().replace(",", "") for c in (m.group(2).split("|") if m else [])]
+        if m and len(cells) >= 4 and m.group(1) not in rows and re.fullmatch(r"[0-9.]+", cells[0]) and re.fullmatch(r"[0-9.]+", cells[3]):
+            try:
+                rows[m.group(1)] = (float(cells[0]), float(cells[1]), float(cells[3]))  # FETCH_SIZE, WRITE_SIZE, SQ_INSTS_VALU
+            except ValueError:
+                pass
+    assert set(rows) == {"quantize_pack", "reduce_requant", "unpack_dequant"}, rows
+    n = 4096 * 4096
+    for k, (fetch, write, valu) in rows.items():
+        assert abs(pc[k]["hbm_bytes_per_launch"] - (2.0 * fetch + write) * 1024) <= 2048, k
+        assert abs(pc[k]["valu_per_element"] - valu * 64 / n) <= 0.06, k
