@@ -35,6 +35,52 @@
 
 namespace fcv2 {
 
+// ---- single instructions whose form matters --------------------------------------------------------------------------
+// Measured on the MI355X (8 waves per SIMD, independent chains): a wave-wide VALU instruction issues in about 2.4
+// cycles when it is a two-operand instruction of a simple class -- and, or, xor, right shift, integer add, fp32
+// add / subtract / multiply, move -- whose operands are vector registers, a literal or an inline constant; in about 3
+// cycles for an fp32 FMA and for v_bitop3 on three vector registers; and in about 4.2 cycles otherwise: anything that
+// reads a SCALAR register, left shifts, the three-operand integer forms, integer min/max/med3, conversions, packed
+// 16-bit, DPP, SDWA, permutes, dot products (reciprocal: 8.3).  The compiler likes to park a constant that is used
+// more than once in a scalar register, which turns the cheapest class into the dearest; the helpers below pin the
+// cheap form.  On the host they are plain C.
+#if defined(__HIP_DEVICE_COMPILE__)
+template <uint32_t C> FCV2_D uint32_t and_lit(uint32_t x) {  // x & C as v_and_b32 with the literal in the instruction
+    uint32_t r;
+    asm("v_and_b32 %0, %1, %2" : "=v"(r) : "n"((int32_t)C), "v"(x));
+    return r;
+}
+template <uint32_t C> FCV2_D uint32_t xor_lit(uint32_t x) {
+    uint32_t r;
+    asm("v_xor_b32 %0, %1, %2" : "=v"(r) : "n"((int32_t)C), "v"(x));
+    return r;
+}
+// A constant held in a vector register the compiler cannot see through (so it cannot move it to a scalar one).
+template <uint32_t C> FCV2_D uint32_t vreg_const() {
+    uint32_t r;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(r) : "n"((int32_t)C));
+    return r;
+}
+// (m & a) | (~m & b) in one v_bitop3 on three vector registers.
+FCV2_D uint32_t bit_select(uint32_t m, uint32_t a, uint32_t b) { return __builtin_amdgcn_bitop3_b32(a, b, m, 0xE4); }
+// (a | b) & m likewise.
+FCV2_D uint32_t or_and(uint32_t a, uint32_t b, uint32_t m) { return __builtin_amdgcn_bitop3_b32(a, b, m, 0xA8); }
+// sum of byte products: a.b0 * w.b0 + ... + a.b3 * w.b3 + c
+FCV2_D uint32_t dot4_u8(uint32_t a, uint32_t w, uint32_t c) { return __builtin_amdgcn_udot4(a, w, c, false); }
+FCV2_D uint32_t rotr32(uint32_t x, int r) { return __builtin_amdgcn_alignbit(x, x, r); }
+#else  // the host pass of the HIP compiler, and the CPU test build
+template <uint32_t C> FCV2_HD uint32_t and_lit(uint32_t x) { return x & C; }
+template <uint32_t C> FCV2_HD uint32_t xor_lit(uint32_t x) { return x ^ C; }
+template <uint32_t C> FCV2_HD uint32_t vreg_const() { return C; }
+FCV2_HD uint32_t bit_select(uint32_t m, uint32_t a, uint32_t b) { return (m & a) | (~m & b); }
+FCV2_HD uint32_t or_and(uint32_t a, uint32_t b, uint32_t m) { return (a | b) & m; }
+FCV2_HD uint32_t dot4_u8(uint32_t a, uint32_t w, uint32_t c) {
+    for (int i = 0; i < 4; ++i) c += ((a >> (8 * i)) & 0xFFu) * ((w >> (8 * i)) & 0xFFu);
+    return c;
+}
+FCV2_HD uint32_t rotr32(uint32_t x, int r) { return (x >> r) | (x << ((32 - r) & 31)); }
+#endif
+
 // ---- plane structure of a b-bit code: widest plane first = most significant bits ---------------------------
 template <int BITS> struct Planes;
 template <> struct Planes<2> { static constexpr int w8 = 0, w4 = 0, w2 = 1, w1 = 0, sh4 = 0, sh2 = 0, sh1 = 0; };
@@ -196,24 +242,23 @@ template <int SH, int BITS> FCV2_HD uint32_t pack_plane4(uint32_t c0, uint32_t c
     return ((a0 >> 8) & 0xFFu) | ((a0 >> 16) & 0xFF00u) | ((a1 << 8) & 0xFF0000u) | (a1 & 0xFF000000u);
 }
 
-// 8 two-bit fields: bits 2i..2i+1 = field of element i (16 bits).
+// 8 two-bit fields: bits 2i..2i+1 = field of element i (16 bits, nothing above them).  The four fields of a register
+// are gathered by one byte dot product with the weights 1, 4, 16, 64 (the masked bytes are field << SH, so the sum is
+// the packed byte << SH).
 template <int SH, int BITS> FCV2_HD uint32_t pack_plane2(uint32_t c0, uint32_t c1) {
-    uint32_t f0 = top_align<2, SH, BITS>(c0), f1 = top_align<2, SH, BITS>(c1);
-    uint32_t a0 = (f0 << 6) | f0, a1 = (f1 << 6) | f1;
-    FCV2_KEEP(a0);
-    FCV2_KEEP(a1);
-    uint32_t b0 = (a0 << 12) | a0, b1 = (a1 << 12) | a1;  // top byte = e0 | e1<<2 | e2<<4 | e3<<6
-    return (b0 >> 24) | ((b1 >> 16) & 0xFF00u);
+    constexpr uint32_t W = 0x40100401u;
+    const uint32_t m0 = (BITS == 2) ? c0 : and_lit<(0x03030303u << SH)>(c0);
+    const uint32_t m1 = (BITS == 2) ? c1 : and_lit<(0x03030303u << SH)>(c1);
+    const uint32_t d0 = dot4_u8(m0, W, 0u), d1 = dot4_u8(m1, W, 0u);
+    return ((d1 << 8) | d0) >> SH;
 }
 
-// 8 one-bit fields: bit i = field of element i (8 bits).
+// 8 one-bit fields: bit i = field of element i (8 bits, nothing above them): two byte dot products with the weights 1, 2, 4, 8 and
+// 16, 32, 64, 128, the second adding to the first.  The 1-bit plane always holds bit 0 of the code.
 template <int SH, int BITS> FCV2_HD uint32_t pack_plane1(uint32_t c0, uint32_t c1) {
-    uint32_t f0 = top_align<1, SH, BITS>(c0), f1 = top_align<1, SH, BITS>(c1);  // bit 7 of every byte
-    uint32_t m = (f0 >> 4) | f1;                                                 // e_i at 8i+3, e_{i+4} at 8i+7
-    uint32_t a = (m << 7) | m;
-    FCV2_KEEP(a);
-    uint32_t b = (a << 14) | a;
-    return b >> 24;
+    static_assert(SH == 0, "the 1-bit plane is the least significant bit of the code");
+    const uint32_t d = dot4_u8(and_lit<0x01010101u>(c0), 0x08040201u, 0u);
+    return dot4_u8(and_lit<0x01010101u>(c1), 0x80402010u, d);
 }
 
 // ---- planes -> codes --------------------------------------------------------------------------------------------
@@ -293,53 +338,79 @@ template <> struct PairMap<2> {  // 2-bit fields at offset 2e: direct for e = 0.
     static constexpr int lo(int k) { return k; }
     static constexpr int hi(int k) { return k + 8; }
     static constexpr int pos(int k) { return k < 5 ? 2 * k : 2 * (k - 5); }
+    static constexpr int k_of(int e) { return e & 7; }       // the register that holds element e ...
+    static constexpr bool in_hi(int e) { return e >= 8; }    // ... and the half of it
 };
 template <> struct PairMap<3> {  // 2-bit field at offset o with the extra bit below it: o = 2, 4, 6, 8
     static constexpr int n_pos = 4;
     static constexpr int lo(int k) { return k + 1; }
     static constexpr int hi(int k) { return (k + 9) & 15; }
     static constexpr int pos(int k) { return 2 * (k & 3) + 1; }
+    static constexpr int k_of(int e) { return (e + 7) & 7; }
+    static constexpr bool in_hi(int e) { return e == 0 || e >= 9; }
 };
 template <> struct PairMap<4> {  // nibbles at offset 0 and 4 of each half, directly and after a rotation by 8
     static constexpr int n_pos = 2;
     static constexpr int lo(int k) { return (k & 3) + 8 * (k >> 2); }
     static constexpr int hi(int k) { return lo(k) + 4; }
     static constexpr int pos(int k) { return 4 * (k & 1); }
+    static constexpr int k_of(int e) { return (e & 3) + 4 * (e >> 3); }
+    static constexpr bool in_hi(int e) { return ((e >> 2) & 1) != 0; }
 };
 
-FCV2_HD uint32_t rotr32(uint32_t x, int r) { return (x >> r) | (x << (32 - r)); }
+template <int BITS> constexpr bool pair_map_consistent() {
+    using M = PairMap<BITS>;
+    for (int k = 0; k < 8; ++k)
+        if (M::k_of(M::lo(k)) != k || M::in_hi(M::lo(k)) || M::k_of(M::hi(k)) != k || !M::in_hi(M::hi(k)) || M::pos(k) + BITS > 10) return false;
+    return true;
+}
+static_assert(pair_map_consistent<2>() && pair_map_consistent<3>() && pair_map_consistent<4>(), "PairMap: element <-> (register, half) maps disagree");
 
+// Every mask below is a literal of a two-operand `and` (see the note on instruction forms at the top), shifts go to
+// the right wherever a plain shift does, and the one wrap-around that is needed (element 0 of the 3-bit layout) is a
+// rotate.
 template <int BITS> FCV2_HD void codes_pairs16(uint32_t p4a, uint32_t p4b, uint32_t p2, uint32_t p1, uint32_t (&Q)[8]) {
     if (BITS == 2) {
-        const uint32_t B = rotr32(p2, 10);  // element 5 at bit 0, 13 at bit 16
-#pragma unroll
-        for (int k = 0; k < 5; ++k) Q[k] = p2 & (0x00030003u << (2 * k));
-#pragma unroll
-        for (int k = 0; k < 3; ++k) Q[5 + k] = B & (0x00030003u << (2 * k));
+        const uint32_t B = p2 >> 10;  // element 5 at bit 0, element 13 at bit 16
+        Q[0] = and_lit<0x00030003u>(p2);
+        Q[1] = and_lit<0x000C000Cu>(p2);
+        Q[2] = and_lit<0x00300030u>(p2);
+        Q[3] = and_lit<0x00C000C0u>(p2);
+        Q[4] = and_lit<0x03000300u>(p2);
+        Q[5] = and_lit<0x00030003u>(B);
+        Q[6] = and_lit<0x000C000Cu>(B);
+        Q[7] = and_lit<0x00300030u>(B);
     } else if (BITS == 3) {
-        // extra bits spread to every second position: bit e -> 2e (and a copy at 2e + 1 that the masks drop)
-        uint32_t x = ((p1 << 8) | p1) & 0x00FF00FFu;
-        x = ((x << 4) | x) & 0x0F0F0F0Fu;
-        x = ((x << 2) | x) & 0x33333333u;
-        x = (x << 1) | x;
-        const uint32_t SA = x >> 1, SB = rotr32(x, 9);  // bit of element e at 2e - 1, resp. at 2e - 9
-        const uint32_t B = rotr32(p2, 8);               // field of element 5 at bit 2, of 13 at bit 18, of 0 at bit 24
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int o = 2 * k + 2;
-            Q[k] = (p2 & (0x00030003u << o)) | (SA & (0x00010001u << (o - 1)));
-            Q[4 + k] = (B & (0x00030003u << o)) | (SB & (0x00010001u << (o - 1)));
-        }
+        // extra bits spread to every second position (bit e -> 2e), then turned right by one: the bit of element e sits
+        // at 2e - 1, directly below the element's 2-bit field at 2e, 2e + 1 (element 0's bit wraps to bit 31)
+        uint32_t x = and_lit<0x00FF00FFu>((p1 << 8) | p1);
+        x = and_lit<0x0F0F0F0Fu>((x << 4) | x);
+        x = and_lit<0x33333333u>((x << 2) | x);
+        x = and_lit<0x55555555u>((x << 1) | x);
+        const uint32_t S = rotr32(x, 1);
+        // even elements: field at 4j, 4j + 1 from the plane, bit at 4j - 1 from S; odd elements: bit at 4j + 1 from S, field
+        // at 4j + 2, 4j + 3 from the plane.  One bit-select each, with the same mask.
+        const uint32_t M = vreg_const<0x33333333u>();
+        const uint32_t We = bit_select(M, p2, S), Wo = bit_select(M, S, p2);
+        const uint32_t We8 = rotr32(We, 8), Wo8 = Wo >> 8;  // elements 6, 8 / 14, 0 and 5, 7 / 13, 15 at the same four positions
+        Q[0] = and_lit<0x000E000Eu>(Wo);   // elements 1, 9    at bit 1
+        Q[1] = and_lit<0x00380038u>(We);   // elements 2, 10   at bit 3
+        Q[2] = and_lit<0x00E000E0u>(Wo);   // elements 3, 11   at bit 5
+        Q[3] = and_lit<0x03800380u>(We);   // elements 4, 12   at bit 7
+        Q[4] = and_lit<0x000E000Eu>(Wo8);  // elements 5, 13
+        Q[5] = and_lit<0x00380038u>(We8);  // elements 6, 14
+        Q[6] = and_lit<0x00E000E0u>(Wo8);  // elements 7, 15
+        Q[7] = and_lit<0x03800380u>(We8);  // elements 8, 0
     } else {
-        const uint32_t Ba = rotr32(p4a, 8), Bb = rotr32(p4b, 8);
-        Q[0] = p4a & 0x000F000Fu;
-        Q[1] = p4a & 0x00F000F0u;
-        Q[2] = Ba & 0x000F000Fu;
-        Q[3] = Ba & 0x00F000F0u;
-        Q[4] = p4b & 0x000F000Fu;
-        Q[5] = p4b & 0x00F000F0u;
-        Q[6] = Bb & 0x000F000Fu;
-        Q[7] = Bb & 0x00F000F0u;
+        const uint32_t Ba = p4a >> 8, Bb = p4b >> 8;
+        Q[0] = and_lit<0x000F000Fu>(p4a);
+        Q[1] = and_lit<0x00F000F0u>(p4a);
+        Q[2] = and_lit<0x000F000Fu>(Ba);
+        Q[3] = and_lit<0x00F000F0u>(Ba);
+        Q[4] = and_lit<0x000F000Fu>(p4b);
+        Q[5] = and_lit<0x00F000F0u>(p4b);
+        Q[6] = and_lit<0x000F000Fu>(Bb);
+        Q[7] = and_lit<0x00F000F0u>(Bb);
     }
 }
 

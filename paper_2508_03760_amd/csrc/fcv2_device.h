@@ -116,10 +116,19 @@ __device__ __forceinline__ uint32_t umed3(uint32_t a, uint32_t b, uint32_t c) {
     return r;
 }
 
-// Running two smallest values (m1 <= m2) of a stream.
-__device__ __forceinline__ void push2(uint32_t& m1, uint32_t& m2, uint32_t c) {
-    m2 = umed3(m1, m2, c);
-    m1 = min(m1, c);
+__device__ __forceinline__ uint32_t umin3(uint32_t a, uint32_t b, uint32_t c) {
+    uint32_t r;
+    asm("v_min3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// Running two smallest values (m1 <= m2) of a stream, two new values at a time: the new second smallest is the smaller
+// of the old one and the median of {m1, x, y} (m1 belongs to the three, so their median is the second smallest of the
+// three; whatever is second smallest overall is either that or the old m2).  Three instructions for two values.
+__device__ __forceinline__ void push2_pair(uint32_t& m1, uint32_t& m2, uint32_t x, uint32_t y) {
+    const uint32_t t = umed3(m1, x, y);
+    m1 = umin3(m1, x, y);
+    m2 = min(m2, t);
 }
 
 // Two smallest values over the LPG lanes of a group (the lanes hold disjoint sets); all lanes get the result.
@@ -180,26 +189,25 @@ __device__ __forceinline__ void quantize_lane(const uint32_t (&w)[EPL / 2], uint
                                               uint32_t (&c)[EPL / 4], GroupMeta& m) {
     const uint32_t lbase = lig * (uint32_t)EPL;
     uint32_t a1, a2, b1, b2;  // two smallest composites (a: minimum side, b: maximum side)
+    const uint32_t key_flip = vreg_const<0x80008000u>();  // in a vector register: the three-register v_bitop3 is the cheap form
 #pragma unroll
     for (int d = 0; d < EPL / 2; ++d) {
         typedef short short2v __attribute__((ext_vector_type(2)));
         const short2v sv = __builtin_bit_cast(short2v, w[d]);
         const uint32_t sign = __builtin_bit_cast(uint32_t, sv >> (short2v){15, 15});
-        const uint32_t k = w[d] ^ (sign | 0x80008000u);  // two order keys
+        const uint32_t k = __builtin_amdgcn_bitop3_b32(sign, w[d], key_flip, 0x36);  // (sign | flip) ^ w: two order keys
         uint32_t e0 = (k << 16) | (uint32_t)(2 * d), e1 = (k & 0xFFFF0000u) | (uint32_t)(2 * d + 1);
         FCV2_KEEP(e0);  // keeps each composite one shift-or / and-or instruction (no regrouping with the xor below)
         FCV2_KEEP(e1);
-        const uint32_t f0 = e0 ^ 0xFFFF0000u, f1 = e1 ^ 0xFFFF0000u;  // inverted key: min finds the largest value
+        const uint32_t f0 = xor_lit<0xFFFF0000u>(e0), f1 = xor_lit<0xFFFF0000u>(e1);  // inverted key: min finds the largest value
         if (d == 0) {
             a1 = min(e0, e1);
             a2 = max(e0, e1);
             b1 = min(f0, f1);
             b2 = max(f0, f1);
         } else if (SR) {
-            push2(a1, a2, e0);
-            push2(a1, a2, e1);
-            push2(b1, b2, f0);
-            push2(b1, b2, f1);
+            push2_pair(a1, a2, e0, e1);
+            push2_pair(b1, b2, f0, f1);
         } else {
             a1 = min(a1, min(e0, e1));
             b1 = min(b1, min(f0, f1));
@@ -353,7 +361,7 @@ template <int BITS, int EPL> __device__ __forceinline__ void store_planes(uint8_
     if (P::w2) {
         uint32_t q[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) q[u] = pack_plane2<P::sh2, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFFFu;
+        for (int u = 0; u < U; ++u) q[u] = pack_plane2<P::sh2, BITS>(c[2 * u], c[2 * u + 1]);
         uint8_t* at = base + (r.plane2 + (uint32_t)(EPL / 4) * L);
         if (U == 4) store_stream(at, make_uint2(q[0] | (q[1] << 16), q[2] | (q[3] << 16)));
         if (U == 2) store_stream(at, q[0] | (q[1] << 16));
@@ -362,7 +370,7 @@ template <int BITS, int EPL> __device__ __forceinline__ void store_planes(uint8_
     if (P::w1) {
         uint32_t q = 0;
 #pragma unroll
-        for (int u = 0; u < U; ++u) q |= (pack_plane1<P::sh1, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFu) << (8 * u);
+        for (int u = 0; u < U; ++u) q |= pack_plane1<P::sh1, BITS>(c[2 * u], c[2 * u + 1]) << (8 * u);
         uint8_t* at = base + (r.plane1 + (uint32_t)(EPL / 8) * L);
         if (U == 4) store_stream(at, q);
         if (U == 2) store_stream(at, (uint16_t)q);

@@ -143,8 +143,8 @@ __device__ __forceinline__ void put_lane(const ST& st, const Rec& rec, uint32_t 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         q4[u] = P::w4 ? pack_plane4<P::sh4, BITS>(c[2 * u], c[2 * u + 1]) : 0u;
-        q2[u] = P::w2 ? (pack_plane2<P::sh2, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFFFu) : 0u;
-        if (P::w1) q1 |= (pack_plane1<P::sh1, BITS>(c[2 * u], c[2 * u + 1]) & 0xFFu) << (8 * u);
+        q2[u] = P::w2 ? pack_plane2<P::sh2, BITS>(c[2 * u], c[2 * u + 1]) : 0u;
+        if (P::w1) q1 |= pack_plane1<P::sh1, BITS>(c[2 * u], c[2 * u + 1]) << (8 * u);
     }
     if (P::w8) {
         st.halves(rec.plane8 + 32u * r, make_uint4(c[0], c[1], c[2], c[3]), make_uint4(c[4], c[5], c[6], c[7]));

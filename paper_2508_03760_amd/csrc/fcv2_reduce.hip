@@ -1,93 +1,173 @@
 // fcv2_reduce.hip -- fcv2_reduce_requant: the local step of the two-step AllReduce (Sections 3.1, 3.4), kernels and launch.
 #include "fcv2_host.h"
 
+// Elements per lane, waves per SIMD at 32 elements per lane, and the way spikes are restored.  Measured on the MI355X on
+// the 16 M-element payload with 8 peers (us per launch at 2 / 3 / 8 bits, one run): 16 elements per lane with the
+// overlay 24.9 / 26.6 / 34.1, with the park 25.5 / 27.2 / 33.6; 32 elements per lane (112 registers, four waves per
+// SIMD) with the overlay 23.6 / 26.9 / 34.8, with the park 27.4 / 29.2 / 34.6; at five waves it spills.  The peer loop
+// costs the same per element either way (the FMA, the add and the unpacking are per element); what 32 elements per lane
+// save in per-lane work they lose in occupancy.
+#ifndef FCV2_REDUCE_EPL
+#define FCV2_REDUCE_EPL(G) 16
+#endif
+#ifndef FCV2_REDUCE_WAVES32
+#define FCV2_REDUCE_WAVES32 4
+#endif
+#ifndef FCV2_REDUCE_PATCH
+#define FCV2_REDUCE_PATCH kPatchOverlay
+#endif
+
 namespace fcv2 {
 
 // Local reduce step.  EPL = 16 elements per lane (groups of 32 are two lanes, larger ones four to sixteen).
 //  - codes are unpacked into 16-bit halves and fed to v_fma_mix_f32 as fp16 denormals (q * 2^-24) against the
 //    scale pre-multiplied by 2^24: the product is the same real number q * scale, the FMA rounds once, so the
 //    result is bit-identical to fma(float(q), scale, lo) without a conversion instruction per element;
-//  - the spike positions of every peer are patched through LDS: the (few) lanes that own a spike of this peer
-//    park their values in a private LDS row, overwrite the spike slots with indexed writes and read the row
-//    back -- a dynamic register index done by memory, paid only by the owners.
-template <int BITS, int EPL>
-__device__ __forceinline__ void dequant_mix(const RawPlanes<EPL>& r, float s, float lo, float (&v)[EPL]) {
+//  - the spikes of every peer are put back through an overlay row in LDS (overlay_spikes below): a dynamic
+//    register index done by memory.
+// Spike restoration (Section 3.3: after dequantization the two spikes of a group go back to their places).  A spike
+// position is a dynamic index into the lane's registers, which only memory can do; each lane has a private row of 16
+// dwords in LDS for it, and a lane's EPL elements are handled 16 at a time.  Two ways, chosen per kernel:
+//   park:    a lane that owns a spike in these 16 elements writes its 16 decoded values to the row, overwrites the
+//            spike slot and reads the row back.  No extra arithmetic, 8 sixteen-byte LDS operations.
+//   overlay: the row is all zero between uses.  The wire format stores code 0 at a spike position, so what the decoder
+//            puts there is t = fma(0, scale, zero), the same for the whole group and known without looking: the owner
+//            writes (spike bits XOR t bits) into the slot, every lane reads its row back and XORs it onto its decoded
+//            values on their way into the accumulators (t ^ spike ^ t = spike, everything else ^ 0 stays), the owner
+//            puts the zero back.  Half the LDS traffic, one cheap XOR per element.  Records whose code at a spike
+//            position is not 0 are malformed; with the overlay their spikes come back wrong.
+// LDS is shared by the four SIMDs of a compute unit and the park's traffic alone fills most of it at the low widths,
+// while the overlay's XORs land on the VALUs, which are the other thing this kernel runs out of.
+constexpr int kPatchPark = 0, kPatchOverlay = 1;
+
+// Which register of Q[8], and which half of it, holds element e of 16; by how much its code is shifted inside the half.
+template <int BITS> struct UnitPairMap {  // codes_pairs on two units of 8: unit u = Q[4u..4u+3], element k and k + 4, at bit 0
+    static constexpr int k_of(int e) { return 4 * (e >> 3) + (e & 3); }
+    static constexpr bool in_hi(int e) { return ((e >> 2) & 1) != 0; }
+    static constexpr int pos(int) { return 0; }
+};
+
+template <int BITS, int EPL, bool SR, int PATCH>
+__device__ __forceinline__ void add_peer_values(const RawPlanes<EPL>& r, const GroupMeta& m, uint32_t lig, uint4* row, float (&acc)[EPL]) {
     typedef _Float16 half2v __attribute__((ext_vector_type(2)));
     using P = Planes<BITS>;
-    if constexpr (EPL == 16 && BITS <= 4) {
-        if (s < 0x1p+100f) {
-            // Narrow codes are only masked in place (code << pos in each half); 2^-pos goes into the multiplier.
-            using M = PairMap<BITS>;
-            uint32_t Q[8];
-            codes_pairs16<BITS>(P::w4 ? r.p4[0] : 0u, P::w4 ? r.p4[EPL / 8 - 1] : 0u, P::w2 ? r.p2[0] : 0u, P::w1 ? r.p1 : 0u, Q);
-            float mult[9];
+    constexpr bool IN_PLACE = BITS <= 4;  // narrow codes are only masked where they stand (codes_pairs16)
+    using M = typename std::conditional<IN_PLACE, PairMap<(IN_PLACE ? BITS : 2)>, UnitPairMap<BITS>>::type;
+    const float s = m.s, lo = m.lo;
+    uint32_t relmin = 0xFFFFFFFFu, relmax = 0xFFFFFFFFu, t = 0u;
+    if (SR) {
+        relmin = (m.si & 0xFFu) - lig * (uint32_t)EPL;  // position inside this lane, or >= EPL when another lane owns the spike
+        relmax = (m.si >> 8) - lig * (uint32_t)EPL;
+        if (PATCH == kPatchOverlay) t = f2u(__fmaf_rn(0.0f, s, lo));  // what a zero code decodes to (-0 offsets, infinite scales included)
+    }
+    const uint32_t smin = m.sv << 16, smax = m.sv & 0xFFFF0000u;
+    u32a* o = reinterpret_cast<u32a*>(row);
+    float mult[9];
 #pragma unroll
-            for (int q = 0; q < 9; ++q) mult[q] = s * __builtin_ldexpf(1.0f, 24 - q);  // only the positions in use survive
+    for (int q = 0; q < 9; ++q) mult[q] = s * __builtin_ldexpf(1.0f, 24 - q);  // only the positions in use survive
+    // The body exists twice: for scales below 2^100 (always, unless the data spans more than that: 2^24 * scale could
+    // overflow) codes go into the mixed-precision FMA as fp16 denormals; otherwise they are converted one by one.
+    auto body = [&](auto fast_tag) {
+    constexpr bool fast = decltype(fast_tag)::value;
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const half2v h = __builtin_bit_cast(half2v, Q[k]);
-                v[M::lo(k)] = __builtin_fmaf((float)h.x, mult[M::pos(k)], lo);
-                v[M::hi(k)] = __builtin_fmaf((float)h.y, mult[M::pos(k)], lo);
+    for (int h = 0; h < EPL / 16; ++h) {
+        const uint32_t rmin = relmin - 16u * h, rmax = relmax - 16u * h;  // the same inside these 16 elements
+        if (SR && PATCH == kPatchOverlay) {
+            if (rmin < 16u) o[rmin] = smin ^ t;
+            if (rmax < 16u) o[rmax] = smax ^ t;
+        }
+        uint32_t Q[8];
+        float qf[16];
+        if constexpr (fast) {
+            if constexpr (IN_PLACE) {
+                const uint32_t p1 = P::w1 ? (EPL == 16 ? r.p1 : (h == 0 ? and_lit<0xFFFFu>(r.p1) : r.p1 >> 16)) : 0u;
+                codes_pairs16<BITS>(P::w4 ? r.p4[(2 * h) % (EPL / 8)] : 0u, P::w4 ? r.p4[(2 * h + 1) % (EPL / 8)] : 0u,
+                                    P::w2 ? r.p2[h % ((EPL + 15) / 16)] : 0u, p1, Q);
+            } else {
+#pragma unroll
+                for (int uu = 0; uu < 2; ++uu) {
+                    const int u = 2 * h + uu;
+                    uint32_t Q4[4];
+                    const uint32_t p4 = P::w4 ? r.p4[u] : 0u;
+                    const uint32_t p2 = P::w2 ? ((r.p2[u >> 1] >> (16 * (u & 1))) & 0xFFFFu) : 0u;
+                    const uint32_t p1 = P::w1 ? ((r.p1 >> (8 * u)) & 0xFFu) : 0u;
+                    codes_pairs<BITS>(P::w8 ? r.p8[2 * u] : 0u, P::w8 ? r.p8[2 * u + 1] : 0u, p4, p2, p1, Q4);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) Q[4 * uu + k] = Q4[k];
+                }
             }
-            return;
+        } else {
+#pragma unroll
+            for (int uu = 0; uu < 2; ++uu) {
+                float q8[8];
+                unit_codes<BITS, EPL>(r, 2 * h + uu, q8);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) qf[8 * uu + j] = q8[j];
+            }
+        }
+        auto value = [&](int e) -> float {  // element e of these 16, decoded
+            if constexpr (!fast) {
+                return __fmaf_rn(qf[e], s, lo);
+            } else {
+                const half2v hh = __builtin_bit_cast(half2v, Q[M::k_of(e)]);
+                return __builtin_fmaf(M::in_hi(e) ? (float)hh.y : (float)hh.x, mult[M::pos(M::k_of(e))], lo);
+            }
+        };
+        if (!SR) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[16 * h + e] = __fadd_rn(acc[16 * h + e], value(e));
+        } else if (PATCH == kPatchOverlay) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {  // a wave's LDS operations execute in issue order: these reads see the writes above
+                const uint4 x4 = row[i];
+                const uint32_t x[4] = {x4.x, x4.y, x4.z, x4.w};
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int e = 4 * i + b;
+                    acc[16 * h + e] = __fadd_rn(acc[16 * h + e], u2f(f2u(value(e)) ^ x[b]));
+                }
+            }
+            if (rmin < 16u) o[rmin] = 0u;  // ... and these zeros land after them
+            if (rmax < 16u) o[rmax] = 0u;
+        } else {
+            float v[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) v[e] = value(e);
+            if (rmin < 16u || rmax < 16u) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) row[i] = make_uint4(f2u(v[4 * i]), f2u(v[4 * i + 1]), f2u(v[4 * i + 2]), f2u(v[4 * i + 3]));
+                if (rmin < 16u) o[rmin] = smin;
+                if (rmax < 16u) o[rmax] = smax;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint4 a = row[i];
+                    v[4 * i] = u2f(a.x);
+                    v[4 * i + 1] = u2f(a.y);
+                    v[4 * i + 2] = u2f(a.z);
+                    v[4 * i + 3] = u2f(a.w);
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[16 * h + e] = __fadd_rn(acc[16 * h + e], v[e]);
         }
     }
-    if (s < 0x1p+100f) {  // always, unless the data spans more than 2^100: then 2^24 * scale could overflow
-        const float s24 = s * 0x1p+24f;
-#pragma unroll
-        for (int u = 0; u < EPL / 8; ++u) {
-            uint32_t Q[4];
-            const uint32_t p4 = P::w4 ? r.p4[u] : 0u;
-            const uint32_t p2 = P::w2 ? ((r.p2[u >> 1] >> (16 * (u & 1))) & 0xFFFFu) : 0u;
-            const uint32_t p1 = P::w1 ? ((r.p1 >> (8 * u)) & 0xFFu) : 0u;
-            codes_pairs<BITS>(P::w8 ? r.p8[2 * u] : 0u, P::w8 ? r.p8[2 * u + 1] : 0u, p4, p2, p1, Q);
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const half2v h = __builtin_bit_cast(half2v, Q[k]);
-                v[8 * u + k] = __builtin_fmaf((float)h.x, s24, lo);
-                v[8 * u + k + 4] = __builtin_fmaf((float)h.y, s24, lo);
-            }
-        }
-    } else {
-#pragma unroll
-        for (int u = 0; u < EPL / 8; ++u) {
-            float q[8];
-            unit_codes<BITS, EPL>(r, u, q);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[8 * u + j] = __fmaf_rn(q[j], s, lo);
-        }
-    }
+    };
+    if (s < 0x1p+100f)
+        body(std::true_type{});
+    else
+        body(std::false_type{});
 }
 
-template <int EPL> __device__ __forceinline__ void patch_spikes(const GroupMeta& m, uint32_t lig, uint4* row, float (&v)[EPL]) {
-    const uint32_t relmin = (m.si & 0xFFu) - lig * (uint32_t)EPL, relmax = (m.si >> 8) - lig * (uint32_t)EPL;
-    if (relmin < (uint32_t)EPL || relmax < (uint32_t)EPL) {
-#pragma unroll
-        for (int i = 0; i < EPL / 4; ++i) row[i] = make_uint4(f2u(v[4 * i]), f2u(v[4 * i + 1]), f2u(v[4 * i + 2]), f2u(v[4 * i + 3]));
-        u32a* o = reinterpret_cast<u32a*>(row);
-        if (relmin < (uint32_t)EPL) o[relmin] = m.sv << 16;
-        if (relmax < (uint32_t)EPL) o[relmax] = m.sv & 0xFFFF0000u;
-#pragma unroll
-        for (int i = 0; i < EPL / 4; ++i) {
-            const uint4 a = row[i];
-            v[4 * i] = u2f(a.x);
-            v[4 * i + 1] = u2f(a.y);
-            v[4 * i + 2] = u2f(a.z);
-            v[4 * i + 3] = u2f(a.w);
-        }
-    }
-}
-
-template <int BITS, int EPL, int LPG, bool SR>
+template <int BITS, int EPL, int LPG, bool SR, int PATCH>
 // Peers are taken two at a time (both peers' loads issued before either is decoded).  Every peer in flight costs
 // about 15 registers; with two the kernel needs 65 to 74 and six or seven waves fit a SIMD, which measured faster
 // than four peers in flight at four or five waves, and faster than one peer at eight.
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(6)))
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(EPL == 32 ? FCV2_REDUCE_WAVES32 : 6)))
 void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
                                                            uint8_t* __restrict__ out, Rec rec_out, float* __restrict__ sum_out,
                                                            uint32_t meta_mode_in, uint32_t meta_mode_out) {
     constexpr int CH = 2;  // peers in flight
-    constexpr int ROW = EPL / 4 + 1;  // uint4 per private patch row, one of padding: conflict-free 16-byte accesses
+    constexpr int ROW = 16 / 4 + 1;  // uint4 per private row of 16 dwords, one of padding: conflict-free 16-byte accesses
     __shared__ uint4 lds[kBlock * ROW];
     __shared__ float tabs[kScaleTables];
     if (meta_mode_in == kMetaInt || meta_mode_out == kMetaInt) fill_scale_tables(tabs);
@@ -95,6 +175,10 @@ void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
     if (L >= n_lanes) return;
     const uint32_t lig = threadIdx.x & (LPG - 1);
     uint4* row = &lds[threadIdx.x * ROW];
+    if (SR && PATCH == kPatchOverlay) {  // the lane's overlay row starts, and is left after every use, all zero
+#pragma unroll
+        for (int i = 0; i < 4; ++i) row[i] = make_uint4(0u, 0u, 0u, 0u);
+    }
     const MetaOffsets mo = meta_offsets<LPG, SR>(rec_in, L, meta_mode_in);
     // -0 is the identity of fp32 addition for every value including -0, so the chain below starts exactly at v_0
     float acc[EPL];
@@ -105,11 +189,7 @@ void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
         constexpr bool INT_META = decltype(int_meta)::value;
         auto add_peer = [&](const RawPlanes<EPL>& r, uint32_t mraw, uint32_t mraw2) {
             const GroupMeta m = spread_meta<LPG, SR, INT_META>(mraw, mraw2, mo, tabs);
-            float v[EPL];
-            dequant_mix<BITS, EPL>(r, m.s, m.lo, v);
-            if (SR) patch_spikes<EPL>(m, lig, row, v);
-#pragma unroll
-            for (int j = 0; j < EPL; ++j) acc[j] = __fadd_rn(acc[j], v[j]);
+            add_peer_values<BITS, EPL, SR, PATCH>(r, m, lig, row, acc);
         };
         int p = 0;
         // CH peers at a time: all loads first, so their latencies overlap
@@ -161,7 +241,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
                                                                  Rec rec_in, uint8_t* __restrict__ out, Rec rec_out,
                                                                  float* __restrict__ sum_out, uint32_t meta_mode_in,
                                                                  uint32_t meta_mode_out) {
-    constexpr int ROW = EPL / 4 + 1;
+    constexpr int ROW = 16 / 4 + 1;
     __shared__ uint4 lds[kBlock * ROW];
     __shared__ float tabs[kScaleTables];
     if (meta_mode_in == kMetaInt || meta_mode_out == kMetaInt) fill_scale_tables(tabs);
@@ -179,12 +259,11 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
         const uint32_t mraw2 = (LPG < 4 && SR) ? ld32(src, mo.at2) : 0u;
         const GroupMeta m = (meta_mode_in == kMetaInt) ? spread_meta<LPG, SR, true>(mraw, mraw2, mo, tabs)
                                                        : spread_meta<LPG, SR, false>(mraw, mraw2, mo, tabs);
-        float v[EPL];
         switch (bits_in) {
 #define FCV2_CASE(B)                                                      \
     case B: {                                                             \
         const RawPlanes<EPL> r = load_planes<B, EPL>(src, rec_in, L);     \
-        dequant_mix<B, EPL>(r, m.s, m.lo, v);                             \
+        add_peer_values<B, EPL, SR, kPatchPark>(r, m, lig, row, acc);     \
         break;                                                            \
     }
             FCV2_CASE(2)
@@ -197,9 +276,6 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
                 FCV2_CASE(8)
 #undef FCV2_CASE
         }
-        if (SR) patch_spikes<EPL>(m, lig, row, v);
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) acc[j] = __fadd_rn(acc[j], v[j]);
     }
     if (sum_out) {
         float4* dst = reinterpret_cast<float4*>(sum_out) + (EPL / 4) * (uint64_t)L;
@@ -219,9 +295,10 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
 template <int BITS, int G, bool SR> struct LaunchReduce {
     static int run(const PeerPtrs& peers, int n_peers, uint64_t n, const Rec& rec_in, void* out, const Rec& rec_out,
                    float* sum_out, uint32_t mf_in, uint32_t mf_out, hipStream_t st) {
-        constexpr int EPL = 16;  // 32 was measured: 180 VGPRs, two waves per SIMD, 15 % slower; 8 doubles the per-lane work
+        constexpr int EPL = FCV2_REDUCE_EPL(G);
+        constexpr int PATCH = FCV2_REDUCE_PATCH;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
-        return launch(k_reduce_requant<BITS, EPL, G / EPL, SR>, dim3(grid_lanes_xcd(n_lanes)), dim3(kBlock), 0, st, peers, n_peers,
+        return launch(k_reduce_requant<BITS, EPL, G / EPL, SR, PATCH>, dim3(grid_lanes_xcd(n_lanes)), dim3(kBlock), 0, st, peers, n_peers,
                       n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
     }
 };

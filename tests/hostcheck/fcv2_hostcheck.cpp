@@ -16,8 +16,8 @@ template <int BITS> static void planes_of_codes(const uint8_t* codes, uint32_t* 
     *p8lo = c0;
     *p8hi = c1;
     *p4 = P::w4 ? pack_plane4<P::sh4, BITS>(c0, c1) : 0;
-    *p2 = P::w2 ? pack_plane2<P::sh2, BITS>(c0, c1) & 0xFFFFu : 0;
-    *p1 = P::w1 ? pack_plane1<P::sh1, BITS>(c0, c1) & 0xFFu : 0;
+    *p2 = P::w2 ? pack_plane2<P::sh2, BITS>(c0, c1) : 0;  // must come back with nothing above bit 15
+    *p1 = P::w1 ? pack_plane1<P::sh1, BITS>(c0, c1) : 0;    // nothing above bit 7
 }
 
 template <int BITS> static void codes_of_planes(uint32_t p4, uint32_t p2, uint32_t p1, uint8_t* codes) {
