@@ -200,19 +200,20 @@ FCV2_D ScaleInt scale_int_from_tables(float s, const float* pow_tab, const float
 // ---- launch plan of the row-staged dispatch kernel (host) ---------------------------------------------------------
 // A block takes `rows` consecutive tokens of `lpr` lanes each (a lane = 32 elements) and has `threads` = their lanes
 // rounded up to whole waves, at most 8 waves.  Its LDS holds a transpose scratch per wave, the packed records, the
-// destination rows and, for integer metadata, the scale tables; 64 KiB at most.  Among the row counts 1..64 that fit,
-// the one with the smallest share of idle lanes wins (the first such).  rows = 0: the shape does not fit the kernel.
+// destination rows, the E expert starts (+ 8 words for the block scan) and, for integer metadata, the scale tables;
+// 64 KiB at most.  Among the row counts 1..64 that fit, the one with the smallest share of idle lanes wins (the first
+// such).  rows = 0: the shape does not fit the kernel.
 constexpr uint32_t kWaveScratchBytes = 5120, kRowsPlanThreadsMax = 512;
 struct RowsPlan {
     uint32_t rows, threads;
     size_t lds_bytes;
 };
-static inline RowsPlan rows_plan(uint32_t lpr, uint32_t K, uint32_t row_bytes, bool int_meta) {
+static inline RowsPlan rows_plan(uint32_t lpr, uint32_t K, uint32_t row_bytes, bool int_meta, uint32_t E) {
     RowsPlan best = {0, 0, 0};
     uint32_t best_idle = ~0u;
     for (uint32_t R = 1; R <= 64 && R * lpr <= kRowsPlanThreadsMax; ++R) {
         const uint32_t waves = (R * lpr + 63) / 64;
-        const size_t lds = (size_t)waves * kWaveScratchBytes + (size_t)R * row_bytes + (size_t)R * K * 4 +
+        const size_t lds = (size_t)waves * kWaveScratchBytes + (size_t)R * row_bytes + (size_t)R * K * 4 + ((size_t)E + 8) * 4 +
                            (int_meta ? (size_t)(kScaleTablePow + kScaleTableThr) * 4 : 0);
         if (lds > 64 * 1024) break;
         const uint32_t idle = (waves * 64 - R * lpr) * 1024 / (waves * 64);  // idle lanes, in 1/1024 of the block

@@ -67,15 +67,16 @@ constexpr int kChunk = 256;  // routed slots per block in the dispatch planning 
 
 struct DispatchWs {  // carving of the dispatch workspace
     uint32_t n_slots, n_chunks;
-    size_t off_hist, off_totals, off_dest, bytes;
+    size_t off_hist, off_totals, off_lrank, off_dest, bytes;
 };
 static DispatchWs dispatch_ws(uint32_t T, uint32_t K, uint32_t E) {
     DispatchWs w;
     w.n_slots = T * K;
     w.n_chunks = (w.n_slots + kChunk - 1) / kChunk;
-    w.off_hist = 0;
-    w.off_totals = round_up((size_t)w.n_chunks * E * 4, 256);
-    w.off_dest = w.off_totals + round_up((size_t)E * 4, 256);
+    w.off_hist = 0;                                                                 // [n_chunks][E] int32
+    w.off_totals = round_up((size_t)w.n_chunks * E * 4, 256);                        // [E] int32
+    w.off_lrank = w.off_totals + round_up((size_t)E * 4, 256);                       // [n_slots] bytes: rank inside the chunk
+    w.off_dest = w.off_lrank + round_up((size_t)w.n_slots, 256);                     // [n_slots] int32: only the direct kernel reads it
     w.bytes = w.off_dest + round_up((size_t)w.n_slots * 4, 256);
     return w;
 }

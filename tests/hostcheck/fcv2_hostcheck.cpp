@@ -144,8 +144,8 @@ int hc_scale_int_estimate(float s) { return scale_int_estimate(s); }
 float hc_scale_of_int(int k) { return scale_of_int(k); }
 
 // Launch plan of the row-staged dispatch kernel: out3 = {rows per block, threads, LDS bytes}.
-void hc_rows_plan(uint32_t lpr, uint32_t K, uint32_t row_bytes, int int_meta, uint64_t* out3) {
-    const RowsPlan p = rows_plan(lpr, K, row_bytes, int_meta != 0);
+void hc_rows_plan(uint32_t lpr, uint32_t K, uint32_t row_bytes, int int_meta, uint32_t E, uint64_t* out3) {
+    const RowsPlan p = rows_plan(lpr, K, row_bytes, int_meta != 0, E);
     out3[0] = p.rows;
     out3[1] = p.threads;
     out3[2] = p.lds_bytes;

@@ -517,6 +517,19 @@ def test_dispatch_quant_ids_outside_the_expert_range_are_dropped():
     assert np.array_equal(send.cpu().numpy()[:R], send_o)
 
 
+@pytest.mark.parametrize("E", [257, 1024, 1025, 2048])
+def test_dispatch_quant_many_experts(E):
+    """More experts than one lane-mask table or one four-word share per lane holds: the planning kernels switch to their
+    general paths (ballot rounds for the in-chunk ranks, looped reads of the expert totals)."""
+    T, H, K = 700, 256, 6
+    x = W.tensor(3, 9, rows=T, cols=H)
+    rng = np.random.default_rng(E)
+    ids = rng.integers(0, E, (T, K)).astype(np.int32)
+    ids[rng.integers(0, T, 40), rng.integers(0, K, 40)] = -1
+    ids[:50, 0] = E - 1  # a run of one expert across wave and chunk borders
+    check_dispatch(x, ids, E, 3, 128, SR, f"dispatch E={E}")
+
+
 def test_dispatch_quant_degenerate_routing():
     T, H, K, E = 130, 512, 8, 256
     x = W.tensor(3, 1, rows=T, cols=H)

@@ -42,7 +42,7 @@ def hc():
     L.hc_scale_of_int.restype = C.c_float
     L.hc_scale_of_int.argtypes = [C.c_int]
     L.hc_rows_plan.restype = None
-    L.hc_rows_plan.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, C.POINTER(C.c_uint64)]
+    L.hc_rows_plan.argtypes = [C.c_uint32, C.c_uint32, C.c_uint32, C.c_int, C.c_uint32, C.POINTER(C.c_uint64)]
     return L
 
 
@@ -260,19 +260,22 @@ def test_bench_byte_formula_is_the_unpadded_record():
 def test_dispatch_launch_plan(hc):
     """The row-staged dispatch kernel's launch shape: whole tokens per block, whole waves, at most 512 threads and
     64 KiB of LDS, the fewest idle lanes; shapes that do not fit get no plan (the direct kernel takes them)."""
-    def plan(lpr, K, row_bytes, int_meta=0):
+    def plan(lpr, K, row_bytes, int_meta=0, E=256):
         out = (C.c_uint64 * 3)()
-        hc.hc_rows_plan(lpr, K, row_bytes, int_meta, out)
+        hc.hc_rows_plan(lpr, K, row_bytes, int_meta, E, out)
         return tuple(int(v) for v in out)
 
+    starts = (256 + 8) * 4  # the block's copy of the expert starts, and the words its scan needs
+
     # the DeepSeek-V3-shaped workload: H = 7168 = 224 lanes, 2-bit rows of 2,352 bytes, 8 copies: two tokens fill 7 waves
-    assert plan(224, 8, 2352) == (2, 448, 7 * 5120 + 2 * 2352 + 2 * 8 * 4)
-    assert plan(256, 8, 2688) == (1, 256, 4 * 5120 + 2688 + 32)      # H = 8192: one token is four whole waves
+    assert plan(224, 8, 2352) == (2, 448, 7 * 5120 + 2 * 2352 + 2 * 8 * 4 + starts)
+    assert plan(256, 8, 2688) == (1, 256, 4 * 5120 + 2688 + 32 + starts)  # H = 8192: one token is four whole waves
     assert plan(128, 8, 1344)[:2] == (1, 128)                         # H = 4096: the first count without idle lanes
     assert plan(1, 2, 32)[:2] == (64, 64)                             # H = 32: 64 tokens share a wave
     assert plan(513, 8, 5000) == (0, 0, 0)                            # more than 512 lanes per token
     assert plan(512, 8, 8 * 5120 + 30000) == (0, 0, 0)                # record too large for the LDS
-    assert plan(224, 8, 2256, 1) == (2, 448, 7 * 5120 + 2 * 2256 + 64 + (258 + 257) * 4)
+    assert plan(224, 8, 2256, 1) == (2, 448, 7 * 5120 + 2 * 2256 + 64 + starts + (258 + 257) * 4)
+    assert plan(224, 8, 2352, 0, 2048)[2] == 7 * 5120 + 2 * 2352 + 64 + (2048 + 8) * 4   # the most experts a call takes
     for lpr in list(range(1, 70)) + [96, 160, 224, 300, 448, 512]:
         for K in (1, 8, 33):
             for row_bytes in (16 * lpr, 40 * lpr + 48):
