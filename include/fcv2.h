@@ -42,6 +42,9 @@
  *   wider than qmax * 2^12.7 or narrower than qmax * 2^-12.8 clip at the ends of the byte.  The mode is the paper's
  *   default for the low widths (Section 4.1: INT2 to INT4) and is accepted at every width for completeness.
  *   FCV2_F_META_FP32 and FCV2_F_META_INT exclude each other.
+ *   With FCV2_F_IDX_BF16 (only together with FCV2_F_SPIKE) the spike positions are stored as BF16 numbers, two bytes each,
+ *   instead of bytes: the first row of Table 4 (4096 INT2 values in groups of 32: 1024 + 512 + 512 + 512 = 2560 bytes;
+ *   the default byte indices give 2304, byte indices with FCV2_F_META_INT the table's second row, 2048).
  */
 #ifndef FCV2_H
 #define FCV2_H
@@ -56,14 +59,14 @@ extern "C" {
 enum {
     FCV2_OK = 0,
     FCV2_ERR_INVALID_ARG = -1, /* null pointer, zero size, size not a multiple of the group, id out of range */
-    FCV2_ERR_UNSUPPORTED = -2, /* bits outside 2..8, group not 32/64/128/256, unknown flag, format pair not built */
+    FCV2_ERR_UNSUPPORTED = -2, /* bits outside 2..8, group not 32/64/128/256, unknown flag or flag pair, format pair not built */
     FCV2_ERR_ALIGN = -3,       /* a device pointer is not 16-byte aligned */
     FCV2_ERR_WORKSPACE = -4,   /* workspace smaller than fcv2_dispatch_workspace_bytes() */
     FCV2_ERR_LAUNCH = -5,      /* the HIP runtime refused the launch */
     FCV2_ERR_SCRATCH = -6      /* the shape needs more than the static scratch of the no-allocation entry point */
 };
 
-enum { FCV2_F_SPIKE = 1u, FCV2_F_META_FP32 = 2u, FCV2_F_META_INT = 4u };
+enum { FCV2_F_SPIKE = 1u, FCV2_F_META_FP32 = 2u, FCV2_F_META_INT = 4u, FCV2_F_IDX_BF16 = 8u };
 enum { FCV2_DT_BF16 = 0, FCV2_DT_FP32 = 1 };
 
 #define FCV2_ABSENT UINT64_MAX
@@ -119,8 +122,8 @@ int fcv2_unpack_dequant_slices(const void* const* records_dev, uint32_t n_slices
  * round the sum to bf16 and quantize it again with fmt_out into packed_out_dev.
  * peers_dev is a HOST array of n_peers DEVICE pointers (copied at call time), 1 <= n_peers <= FCV2_MAX_PEERS.
  * sum_out_dev, if not NULL, receives the n fp32 sums (before the bf16 rounding).
- * fmt_in and fmt_out must agree in group and FCV2_F_SPIKE (bits and the metadata flags may differ; equal bits take
- * the fast kernel); other pairs give FCV2_ERR_UNSUPPORTED. */
+ * fmt_in and fmt_out must agree in group and FCV2_F_SPIKE (bits, the metadata flags and the index width may differ; equal
+ * bits take the fast kernel); other pairs give FCV2_ERR_UNSUPPORTED. */
 int fcv2_reduce_requant(const void* const* peers_dev, int n_peers, uint64_t n, const fcv2_fmt_t* fmt_in,
                         const fcv2_fmt_t* fmt_out, void* packed_out_dev, float* sum_out_dev, void* hip_stream);
 

@@ -15,6 +15,8 @@
 //     (a float offset, exact in bf16 because it is an input value);
 //   * widest plane holds the most-significant bits ("first 4 bits" of Fig. 3); inside a plane byte
 //     the element with the lowest index sits in the least-significant bits;
+//   * spike indices are bytes (Section 3.3: "INT8"); with ORC_F_IDX_BF16 they are the positions written as BF16
+//     numbers, two bytes each, which is the first row of Table 4 (2560 bytes for 4096 INT2 values in groups of 32);
 //   * integer metadata (Eq. 1, Table 4 second row; flag ORC_F_META_INT): one signed byte
 //     scale_int = round(log2(scale) * 10) clamped to [-128, 127], decoded as 2^(scale_int / 10) rounded to
 //     fp32; one unsigned byte zero = the usual integer zero-point round(-lo / scale) over a range widened to
@@ -58,8 +60,9 @@ int plane_widths(uint32_t bits, int w[3]) {
 
 bool fmt_ok(const orc_fmt* f) {
     return f && f->bits >= 2 && f->bits <= 8 && f->group >= 3 && f->group <= 256 &&
-           (f->flags & ~(ORC_F_SPIKE | ORC_F_META_FP32 | ORC_F_META_INT)) == 0 &&
-           (f->flags & (ORC_F_META_FP32 | ORC_F_META_INT)) != (ORC_F_META_FP32 | ORC_F_META_INT);
+           (f->flags & ~(ORC_F_SPIKE | ORC_F_META_FP32 | ORC_F_META_INT | ORC_F_IDX_BF16)) == 0 &&
+           (f->flags & (ORC_F_META_FP32 | ORC_F_META_INT)) != (ORC_F_META_FP32 | ORC_F_META_INT) &&
+           (!(f->flags & ORC_F_IDX_BF16) || (f->flags & ORC_F_SPIKE));  // index width means something only with spikes
 }
 
 uint64_t plane_offset(const orc_layout& L, int width) {
@@ -116,7 +119,7 @@ int orc_get_layout(uint64_t n, const orc_fmt* fmt, uint32_t align, orc_layout* L
         off += L->n_groups * 2 * 2;
         off = round_up(off, align);
         L->off_spike_idx = off;
-        off += L->n_groups * 2;
+        off += L->n_groups * 2 * ((fmt->flags & ORC_F_IDX_BF16) ? 2 : 1);  // Table 4: indices in BF16 (first row) or INT8
     }
     L->total_bytes = round_up(off, align);  // records follow each other at aligned addresses
     return ORC_OK;
@@ -303,7 +306,13 @@ int orc_quantize_pack(const uint16_t* x, uint64_t n, const orc_fmt* fmt, uint32_
         }
         if (fmt->flags & ORC_F_SPIKE) {
             std::memcpy(packed + L.off_spike_val + 4 * g, sv, 4);
-            std::memcpy(packed + L.off_spike_idx + 2 * g, si, 2);
+            if (fmt->flags & ORC_F_IDX_BF16) {
+                // the position as a BF16 number (Table 4, first row): exact, positions are below 256
+                const uint16_t ib[2] = {orc_bf16_rne((float)si[0]), orc_bf16_rne((float)si[1])};
+                std::memcpy(packed + L.off_spike_idx + 4 * g, ib, 4);
+            } else {
+                std::memcpy(packed + L.off_spike_idx + 2 * g, si, 2);
+            }
         }
     }
     return orc_split_pack(codes.data(), n, fmt, align, packed);
@@ -343,8 +352,20 @@ static int decode_f32(const uint8_t* packed, uint64_t n, const orc_fmt* fmt, uin
             uint16_t sv[2];
             uint8_t si[2];
             std::memcpy(sv, packed + L.off_spike_val + 4 * g, 4);
-            std::memcpy(si, packed + L.off_spike_idx + 2 * g, 2);
+            bool is_position[2] = {true, true};
+            if (fmt->flags & ORC_F_IDX_BF16) {
+                uint16_t ib[2];
+                std::memcpy(ib, packed + L.off_spike_idx + 4 * g, 4);
+                for (int k = 0; k < 2; ++k) {
+                    const float pos = bf16_to_f32(ib[k]);
+                    is_position[k] = pos >= 0.0f && pos < 256.0f && pos == std::floor(pos);
+                    si[k] = is_position[k] ? (uint8_t)pos : 0;
+                }
+            } else {
+                std::memcpy(si, packed + L.off_spike_idx + 2 * g, 2);
+            }
             for (int k = 0; k < 2; ++k) {
+                if (!is_position[k]) continue;  // malformed record: leave the dequantized value
                 if (si[k] >= G) continue;  // malformed record: leave the dequantized value
                 v[g * G + si[k]] = bf16_to_f32(sv[k]);
                 if (is_spike) {

@@ -12,7 +12,7 @@
  *   - bit splitting: a b-bit code stored as byte-aligned 4/2/1-bit planes   (Section 3.2, Fig. 3)
  *   - spike reserving: group min and max kept in float form with their
  *     in-group indices, the rest quantized over the shrunk range            (Section 3.3, Fig. 5)
- *   - metadata section sizes                                               (Section 3.3, Table 4)
+ *   - metadata section sizes, spike indices as INT8 or as BF16 numbers      (Section 3.3, Table 4)
  *   - integer metadata: the scale as one byte, scale_int = round(log2(scale) * 10),
  *     and a one-byte zero                                                  (Section 3.3, Eq. 1, Table 4)
  *   - local dequantize-sum-requantize step of the two-step AllReduce        (Sections 3.1, 3.4)
@@ -38,7 +38,7 @@ extern "C" {
 #endif
 
 enum { ORC_OK = 0, ORC_ERR_ARG = -1 };
-enum { ORC_F_SPIKE = 1u, ORC_F_META_FP32 = 2u, ORC_F_META_INT = 4u };
+enum { ORC_F_SPIKE = 1u, ORC_F_META_FP32 = 2u, ORC_F_META_INT = 4u, ORC_F_IDX_BF16 = 8u };
 enum { ORC_DT_BF16 = 0, ORC_DT_FP32 = 1 };
 
 typedef struct {

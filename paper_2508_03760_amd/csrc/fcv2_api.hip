@@ -13,12 +13,13 @@ __global__ __launch_bounds__(kBlock) void k_stream_copy(const uint4* __restrict_
 static bool fmt_supported(const fcv2_fmt_t* f) {
     if (f->bits < 2 || f->bits > 8) return false;
     if (f->group != 32 && f->group != 64 && f->group != 128 && f->group != 256) return false;
-    if ((f->flags & ~(FCV2_F_SPIKE | FCV2_F_META_FP32 | FCV2_F_META_INT)) != 0) return false;
+    if ((f->flags & ~(FCV2_F_SPIKE | FCV2_F_META_FP32 | FCV2_F_META_INT | FCV2_F_IDX_BF16)) != 0) return false;
+    if ((f->flags & FCV2_F_IDX_BF16) && !(f->flags & FCV2_F_SPIKE)) return false;  // index width means something only with spikes
     return (f->flags & (FCV2_F_META_FP32 | FCV2_F_META_INT)) != (FCV2_F_META_FP32 | FCV2_F_META_INT);  // one or the other
 }
 
 
-static Rec rec_of(const fcv2_layout_t& l) {
+static Rec rec_of(const fcv2_layout_t& l, const fcv2_fmt_t* fmt) {
     auto rel = [](uint64_t o) { return o == FCV2_ABSENT ? 0u : (uint32_t)o; };
     Rec r;
     r.plane8 = rel(l.off_plane8);
@@ -30,6 +31,7 @@ static Rec rec_of(const fcv2_layout_t& l) {
     r.spike_val = rel(l.off_spike_val);
     r.spike_idx = rel(l.off_spike_idx);
     r.total = (uint32_t)l.total_bytes;
+    r.idx_bf16 = (fmt->flags & FCV2_F_IDX_BF16) ? 1u : 0u;
     return r;
 }
 
@@ -57,7 +59,7 @@ int dispatch_checked(const void* x, const int32_t* ids, uint32_t T, uint32_t H, 
     if (!aligned16(x) || !aligned16(send) || !aligned16(ws) || ((uintptr_t)ids & 3u) || ((uintptr_t)expert_offsets & 3u) ||
         ((uintptr_t)row_src & 3u))
         return FCV2_ERR_ALIGN;
-    return launch_dispatch(fmt, x, ids, T, H, K, E, (uint8_t*)send, expert_offsets, row_src, ws, rec_of(l), (uint32_t)l.total_bytes,
+    return launch_dispatch(fmt, x, ids, T, H, K, E, (uint8_t*)send, expert_offsets, row_src, ws, rec_of(l, fmt), (uint32_t)l.total_bytes,
                            (hipStream_t)stream);
 }
 
@@ -109,7 +111,7 @@ int fcv2_get_layout(uint64_t n, const fcv2_fmt_t* fmt, uint32_t align, fcv2_layo
     out->off_scale = take(true, ng * meta);
     out->off_zero = take(true, ng * meta);
     out->off_spike_val = take((fmt->flags & FCV2_F_SPIKE) != 0, ng * 4);
-    out->off_spike_idx = take((fmt->flags & FCV2_F_SPIKE) != 0, ng * 2);
+    out->off_spike_idx = take((fmt->flags & FCV2_F_SPIKE) != 0, ng * ((fmt->flags & FCV2_F_IDX_BF16) ? 4 : 2));
     out->total_bytes = round_up(off, align);  // the next record starts aligned too
     return FCV2_OK;
 }
@@ -133,7 +135,7 @@ int fcv2_quantize_pack_slices(const void* x, uint64_t n, uint32_t n_slices, cons
     if (rc != FCV2_OK) return rc;
     if (n_slices > 1 && (record_stride < l.total_bytes || record_stride % FCV2_TENSOR_ALIGN != 0)) return FCV2_ERR_INVALID_ARG;
     if (!aligned16(x) || !aligned16(packed)) return FCV2_ERR_ALIGN;
-    return launch_quantize(fmt, x, n, packed, rec_of(l), n_slices, record_stride, (hipStream_t)stream);
+    return launch_quantize(fmt, x, n, packed, rec_of(l, fmt), n_slices, record_stride, (hipStream_t)stream);
 }
 
 int fcv2_quantize_pack(const void* x, uint64_t n, const fcv2_fmt_t* fmt, void* packed, void* stream) {
@@ -155,7 +157,7 @@ int fcv2_unpack_dequant_slices(const void* const* records, uint32_t n_slices, ui
         if (!aligned16(ptr)) return FCV2_ERR_ALIGN;
         pp.base[p] = (const uint8_t*)ptr;
     }
-    return launch_unpack(fmt, pp, n_slices, rec_of(l), n, out, (uint32_t)(out_dtype == FCV2_DT_FP32), (hipStream_t)stream);
+    return launch_unpack(fmt, pp, n_slices, rec_of(l, fmt), n, out, (uint32_t)(out_dtype == FCV2_DT_FP32), (hipStream_t)stream);
 }
 
 int fcv2_unpack_dequant(const void* packed, uint64_t n, const fcv2_fmt_t* fmt, void* out, int out_dtype, void* stream) {
@@ -184,7 +186,7 @@ int fcv2_reduce_requant(const void* const* peers, int n_peers, uint64_t n, const
         if (!aligned16(ptr)) return FCV2_ERR_ALIGN;
         pp.base[p] = (const uint8_t*)ptr;
     }
-    return launch_reduce(fmt_in, fmt_out, pp, n_peers, n, rec_of(lin), packed_out, rec_of(lout), sum_out, (hipStream_t)stream);
+    return launch_reduce(fmt_in, fmt_out, pp, n_peers, n, rec_of(lin, fmt_in), packed_out, rec_of(lout, fmt_out), sum_out, (hipStream_t)stream);
 }
 
 int fcv2_dispatch_workspace_bytes(uint32_t T, uint32_t K, uint32_t E, size_t* out) {

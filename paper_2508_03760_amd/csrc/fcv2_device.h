@@ -32,6 +32,7 @@ namespace fcv2 {
 struct Rec {  // section offsets of one packed record, relative to its first byte (records are < 4 GiB)
     uint32_t plane8, plane4, plane2, plane1, scale, zero, spike_val, spike_idx;
     uint32_t total;  // bytes of the record
+    uint32_t idx_bf16;  // spike positions stored as BF16 numbers, two bytes each (Table 4, first row), instead of bytes
 };
 
 struct PeerPtrs {
@@ -168,6 +169,19 @@ __device__ __forceinline__ float rcp_newton(float s) {
     const float y0 = __builtin_amdgcn_rcpf(s);
     const float e = __fmaf_rn(-s, y0, 1.0f);
     return __fmaf_rn(e, y0, y0);
+}
+
+// Spike positions as the wire stores them with FCV2_F_IDX_BF16: the two positions (min | max << 8, each below 256) as two
+// BF16 numbers (min in the low half).  Exact both ways: a position has at most 8 significant bits.
+__device__ __forceinline__ uint32_t idx_pair_to_bf16(uint32_t si) {
+    return (__float_as_uint((float)(si & 0xFFu)) >> 16) | (__float_as_uint((float)((si >> 8) & 0xFFu)) & 0xFFFF0000u);
+}
+// Back.  A well-formed record holds whole numbers below the group size here; anything else is a malformed record and
+// outside the contract (values outside [0, 256) are read as position 255, fractions are cut off).
+__device__ __forceinline__ uint32_t idx_pair_of_bf16(uint32_t raw) {
+    const float a = __uint_as_float(raw << 16), b = __uint_as_float(raw & 0xFFFF0000u);
+    const uint32_t ia = (a >= 0.0f && a < 256.0f) ? (uint32_t)a : 0xFFu, ib = (b >= 0.0f && b < 256.0f) ? (uint32_t)b : 0xFFu;
+    return ia | (ib << 8);
 }
 
 // Two fp32 -> packed bf16, round to nearest even (v_cvt_pk_bf16_f32).
@@ -391,7 +405,10 @@ template <bool SR> __device__ __forceinline__ void store_meta(uint8_t* base, con
     }
     if (SR) {
         *reinterpret_cast<uint32_t*>(base + (r.spike_val + 4u * g)) = m.sv;
-        *reinterpret_cast<uint16_t*>(base + (r.spike_idx + 2u * g)) = (uint16_t)m.si;
+        if (r.idx_bf16)
+            *reinterpret_cast<uint32_t*>(base + (r.spike_idx + 4u * g)) = idx_pair_to_bf16(m.si);
+        else
+            *reinterpret_cast<uint16_t*>(base + (r.spike_idx + 2u * g)) = (uint16_t)m.si;
     }
 }
 
@@ -538,13 +555,13 @@ __device__ __forceinline__ void meta_item(const Rec& r, uint32_t g, uint32_t mod
     uint32_t at = r.scale + msz * g;
     if (kind == 1u) at = r.zero + msz * g;
     if (kind == 2u) at = r.spike_val + 4u * g;
-    if (kind == 3u) at = r.spike_idx + 2u * g;
+    if (kind == 3u) at = r.idx_bf16 ? r.spike_idx + 4u * g : r.spike_idx + 2u * g;
     const uint32_t b0 = 4u + (at & 3u), b1 = b0 + 1u;
     uint32_t s = 0x07060504u;                                                 // fp32 items, spike values: as loaded
     if (mode == kMetaBf16) s = 0x00000C0Cu | (b0 << 16) | (b1 << 24);         // bf16 -> the upper half: fp32 bits
     if (mode == kMetaInt) s = 0x0C0C0C00u | b0;                               // one byte -> the low byte
     if (kind == 2u) s = 0x07060504u;
-    if (kind == 3u) s = 0x0C0C0000u | (b1 << 8) | b0;                         // two index bytes -> the low half
+    if (kind == 3u) s = r.idx_bf16 ? 0x07060504u : (0x0C0C0000u | (b1 << 8) | b0);  // two index bytes -> the low half (two BF16: as loaded)
     at_dword = at & ~3u;
     sel = s;
 }
@@ -571,7 +588,7 @@ template <int ODD> __device__ __forceinline__ uint32_t pair_bcast(uint32_t v) {
 }
 
 template <int LPG, bool SR, bool INT_META>
-__device__ __forceinline__ GroupMeta spread_meta(uint32_t raw, uint32_t raw2, const MetaOffsets& o, const float* tabs) {
+__device__ __forceinline__ GroupMeta spread_meta(uint32_t raw, uint32_t raw2, const MetaOffsets& o, const float* tabs, uint32_t idx_bf16) {
     const uint32_t val = __builtin_amdgcn_perm(raw, 0u, o.sel);
     GroupMeta m;
     uint32_t sb, zb;
@@ -594,6 +611,7 @@ __device__ __forceinline__ GroupMeta spread_meta(uint32_t raw, uint32_t raw2, co
         m.s = u2f(sb);
         m.lo = u2f(zb);
     }
+    if (SR && idx_bf16) m.si = idx_pair_of_bf16(m.si);  // uniform branch: the positions travel as two BF16 numbers
     m.raw_s = m.raw_z = 0;
     return m;
 }

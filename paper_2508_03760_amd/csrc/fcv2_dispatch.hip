@@ -248,7 +248,10 @@ __device__ __forceinline__ void put_lane(const ST& st, const Rec& rec, uint32_t 
         }
         if (SR) {
             st.meta(rec.spike_val + 4u * g, m.sv);
-            st.meta(rec.spike_idx + 2u * g, (uint16_t)m.si);
+            if (rec.idx_bf16)
+                st.meta(rec.spike_idx + 4u * g, idx_pair_to_bf16(m.si));
+            else
+                st.meta(rec.spike_idx + 2u * g, (uint16_t)m.si);
         }
     }
 }

@@ -188,7 +188,7 @@ void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
     auto sum_peers = [&](auto int_meta) {
         constexpr bool INT_META = decltype(int_meta)::value;
         auto add_peer = [&](const RawPlanes<EPL>& r, uint32_t mraw, uint32_t mraw2) {
-            const GroupMeta m = spread_meta<LPG, SR, INT_META>(mraw, mraw2, mo, tabs);
+            const GroupMeta m = spread_meta<LPG, SR, INT_META>(mraw, mraw2, mo, tabs, rec_in.idx_bf16);
             add_peer_values<BITS, EPL, SR, PATCH>(r, m, lig, row, acc);
         };
         int p = 0;
@@ -257,8 +257,8 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
         const BufferSrc src = buffer_src(peers.base[p], rec_in.total);
         const uint32_t mraw = ld32(src, mo.at);
         const uint32_t mraw2 = (LPG < 4 && SR) ? ld32(src, mo.at2) : 0u;
-        const GroupMeta m = (meta_mode_in == kMetaInt) ? spread_meta<LPG, SR, true>(mraw, mraw2, mo, tabs)
-                                                       : spread_meta<LPG, SR, false>(mraw, mraw2, mo, tabs);
+        const GroupMeta m = (meta_mode_in == kMetaInt) ? spread_meta<LPG, SR, true>(mraw, mraw2, mo, tabs, rec_in.idx_bf16)
+                                                       : spread_meta<LPG, SR, false>(mraw, mraw2, mo, tabs, rec_in.idx_bf16);
         switch (bits_in) {
 #define FCV2_CASE(B)                                                      \
     case B: {                                                             \

@@ -39,7 +39,8 @@ __global__ __launch_bounds__(kBlock) void k_unpack_dequant_t(PeerPtrs records, u
         uint32_t sv = 0, si = 0;
         if (SR) {
             sv = *reinterpret_cast<const uint32_t*>(in + (rec.spike_val + 4u * g));
-            si = *reinterpret_cast<const uint16_t*>(in + (rec.spike_idx + 2u * g));
+            si = rec.idx_bf16 ? idx_pair_of_bf16(*reinterpret_cast<const uint32_t*>(in + (rec.spike_idx + 4u * g)))
+                              : (uint32_t) * reinterpret_cast<const uint16_t*>(in + (rec.spike_idx + 2u * g));
         }
 #pragma unroll
         for (int u = 0; u < EPL / 8; ++u) {

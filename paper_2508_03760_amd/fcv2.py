@@ -14,6 +14,7 @@ from . import build as _build
 F_SPIKE = 1
 F_META_FP32 = 2
 F_META_INT = 4
+F_IDX_BF16 = 8
 DT_BF16 = 0
 DT_FP32 = 1
 ABSENT = 2**64 - 1

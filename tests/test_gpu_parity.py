@@ -12,7 +12,7 @@ from paper_2508_03760_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
 
-SR, F32, INT = fcv2.F_SPIKE, fcv2.F_META_FP32, fcv2.F_META_INT
+SR, F32, INT, IDX16 = fcv2.F_SPIKE, fcv2.F_META_FP32, fcv2.F_META_INT, fcv2.F_IDX_BF16
 DEV = "cuda:0"
 
 
@@ -37,7 +37,7 @@ def sections(L, flags):
             out.append((f"plane{w}", off, L.n * w // 8))
     out += [("scale", L.off_scale, m * L.n_groups), ("zero", L.off_zero, m * L.n_groups)]
     if flags & SR:
-        out += [("spike_val", L.off_spike_val, 4 * L.n_groups), ("spike_idx", L.off_spike_idx, 2 * L.n_groups)]
+        out += [("spike_val", L.off_spike_val, 4 * L.n_groups), ("spike_idx", L.off_spike_idx, (4 if flags & IDX16 else 2) * L.n_groups)]
     return out
 
 
@@ -83,7 +83,7 @@ def check_codec(x_u16, bits, group, flags, what):
 def test_codec_all_formats(bits, group):
     n = 2048 * 3 + 3 * 256  # three full 256-lane blocks plus a partial one
     x = W.tensor(2, 0, rows=1, cols=n).reshape(-1)
-    for flags in (SR, 0, SR | F32, F32, SR | INT, INT):
+    for flags in (SR, 0, SR | F32, F32, SR | INT, INT, SR | IDX16, SR | INT | IDX16):
         check_codec(x, bits, group, flags, f"b{bits} g{group} f{flags}")
 
 
@@ -93,6 +93,11 @@ def test_codec_single_group_and_tiny_inputs(bits):
         for ngroups in (1, 2, 7):
             x = W.tensor(4, 1, rows=1, cols=group * ngroups).reshape(-1)
             check_codec(x, bits, group, SR, f"tiny b{bits} g{group} x{ngroups}")
+
+
+def test_table4_rows_are_layouts_of_the_library():
+    assert fcv2.get_layout(4096, 2, 32, SR | IDX16, 1).total_bytes == 2560  # Table 4, first row
+    assert fcv2.get_layout(4096, 2, 32, SR | INT, 1).total_bytes == 2048    # second row
 
 
 def _edge_groups(group):
@@ -122,7 +127,7 @@ def _edge_groups(group):
 @pytest.mark.parametrize("group", [32, 64, 128, 256])
 def test_codec_edge_cases(bits, group):
     x = _edge_groups(group)
-    for flags in (SR, 0, SR | F32, SR | INT, INT):
+    for flags in (SR, 0, SR | F32, SR | INT, INT, SR | IDX16):
         check_codec(x, bits, group, flags, f"edge b{bits} g{group} f{flags}")
 
 
@@ -239,6 +244,8 @@ def test_reduce_requant_all_formats(bits, group):
     check_reduce(xs, bits, group, SR, f"b{bits} g{group} N8")
     check_reduce(xs[:3], bits, group, 0, f"b{bits} g{group} N3 no-sr")
     check_reduce(xs[:5], bits, group, SR | INT, f"b{bits} g{group} N5 integer metadata")
+    check_reduce(xs[:4], bits, group, SR | IDX16, f"b{bits} g{group} N4 BF16 positions")
+    check_reduce(xs[:2], bits, group, SR | IDX16, f"b{bits} g{group} N2 BF16 positions in, bytes out", flags_out=SR)
 
 
 @pytest.mark.parametrize("flags_in", [0, SR, SR | F32])
@@ -418,7 +425,7 @@ def check_dispatch(x, ids, E, bits, group, flags, what):
 
 
 @pytest.mark.parametrize("bits,group,flags", [(2, 128, SR), (3, 32, SR), (4, 64, 0), (5, 128, SR | F32), (7, 256, SR), (8, 128, SR),
-                                              (2, 32, SR | INT), (4, 128, INT)])
+                                              (2, 32, SR | INT), (4, 128, INT), (2, 32, SR | IDX16), (6, 256, SR | INT | IDX16)])
 def test_dispatch_quant_small(bits, group, flags):
     T, H, K, E = 300, 768, 4, 40  # slots not a multiple of the planning chunk, rows not a multiple of a block
     x = W.tensor(3, 0, rows=T, cols=H)
@@ -586,10 +593,12 @@ def test_workload2_full(bits):
 
 
 def test_workload2_paper_default_low_bit_shape():
-    """Section 4.1's default for INT2: groups of 32, spike reserving, integer scale and zero (Eq. 1, Table 4)."""
+    """Section 4.1's default for INT2: groups of 32, spike reserving, integer scale and zero (Eq. 1, Table 4); and the
+    table's first row (bf16 scale and zero, spike positions as BF16 numbers) on the sender and the receiver."""
     xs = [W.tensor(2, p).reshape(-1) for p in range(8)]
     check_codec(xs[0], 2, 32, SR | INT, "workload 2 b2 g32 integer meta")
     check_reduce(xs, 2, 32, SR | INT, "workload 2 b2 g32 integer meta N8")
+    check_codec(xs[0], 2, 32, SR | IDX16, "workload 2 b2 g32 BF16 positions")
 
 
 def test_workload3_full():

@@ -72,7 +72,7 @@ def test_get_layout_matches_oracle_and_rejects_bad_input(lib):
     from paper_2508_03760_amd import fcv2
     for bits in range(2, 9):
         for group in (32, 64, 128, 256):
-            for flags in (0, 1, 2, 3, 4, 5):
+            for flags in (0, 1, 2, 3, 4, 5, 9, 11, 13):
                 for align in (16, 256):
                     for n in (group, 4096, 7168 * 4):
                         if n % group:
@@ -89,7 +89,11 @@ def test_get_layout_matches_oracle_and_rejects_bad_input(lib):
     with pytest.raises(fcv2.Fcv2Error):
         fcv2.get_layout(0, 4, 128, 1)
     with pytest.raises(fcv2.Fcv2Error):
-        fcv2.get_layout(4096, 4, 128, 8)
+        fcv2.get_layout(4096, 4, 128, 16)  # unknown flag
+    with pytest.raises(fcv2.Fcv2Error):
+        fcv2.get_layout(4096, 4, 128, 8)  # BF16 spike positions without spikes
+    with pytest.raises(ValueError):
+        O.get_layout(4096, 4, 128, 8)
     with pytest.raises(fcv2.Fcv2Error):
         fcv2.get_layout(4096, 4, 128, 1, 48)
     with pytest.raises(fcv2.Fcv2Error):

@@ -70,7 +70,36 @@ def test_table4_footprint():
     assert (L.off_spike_idx - L.off_spike_val) + byte_idx == rows["scale_int"][3]  # 768: byte indices
     assert (L.off_spike_idx - L.off_spike_val) + 2 * byte_idx == spikes  # 1024 with 2-byte indices
     assert quant + sz + spikes == total and sz + spikes == meta
-    assert L.total_bytes == quant + sz + rows["scale_int"][3]  # this build: bf16 scale/zero, byte indices
+    assert L.total_bytes == quant + sz + rows["scale_int"][3]  # the default format: bf16 scale/zero, byte indices
+    # the table's first row as a layout of its own: spike positions as BF16 numbers, two bytes each
+    L1 = O.get_layout(4096, 2, 32, SR | O.F_IDX_BF16, align=1)
+    assert L1.total_bytes == total == 2560
+    assert (L1.off_plane2, L1.off_scale, L1.off_zero, L1.off_spike_val, L1.off_spike_idx) == (0, 1024, 1280, 1536, 2048)
+    assert L1.total_bytes - L1.off_spike_val == spikes and L1.total_bytes - L1.off_scale == meta
+
+
+def test_spike_positions_as_bf16_numbers():
+    """Table 4, first row: the positions written as BF16 numbers.  Nothing else in the record changes, the numbers are
+    exactly the byte positions, and decoding gives the same values as with byte positions."""
+    rng = np.random.default_rng(8)
+    for bits, G in ((2, 32), (3, 64), (4, 128), (8, 256)):
+        n = G * 40
+        x = bf(rng.standard_normal(n) * np.exp(rng.standard_normal(n)))
+        a = O.quantize_pack(x, bits, G, SR)
+        b = O.quantize_pack(x, bits, G, SR | O.F_IDX_BF16)
+        La, Lb = O.get_layout(n, bits, G, SR), O.get_layout(n, bits, G, SR | O.F_IDX_BF16)
+        assert Lb.off_spike_idx == La.off_spike_idx and Lb.total_bytes >= La.total_bytes
+        assert np.array_equal(a[:La.off_spike_idx], b[:Lb.off_spike_idx])  # planes, scale, zero, spike values
+        pos_bytes = a[La.off_spike_idx:La.off_spike_idx + 2 * La.n_groups]
+        pos_bf16 = f32(b[Lb.off_spike_idx:Lb.off_spike_idx + 4 * Lb.n_groups].view(np.uint16))
+        assert np.array_equal(pos_bf16, pos_bytes.astype(np.float32))
+        va = O.unpack_dequant(a, n, bits, G, SR)
+        vb = O.unpack_dequant(b, n, bits, G, SR | O.F_IDX_BF16)
+        assert np.array_equal(va.view(np.uint32), vb.view(np.uint32))
+        # the reduce step reads either kind and writes either kind
+        r1 = O.reduce_requant([b, b], n, (bits, G, SR | O.F_IDX_BF16), (bits, G, SR))
+        r2 = O.reduce_requant([a, a], n, (bits, G, SR))
+        assert np.array_equal(r1, r2)
 
 
 @pytest.mark.parametrize("bits", range(2, 9))
