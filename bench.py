@@ -533,6 +533,11 @@ def main():
             dt_mt = (time.perf_counter() - t) / reps_mt
         cpu["all_cores"] = dict(value=round(total_bytes / dt_mt / 1e9, 4), unit="GB/s", cores=n_thr,
                                 sample=f"{reps_mt} steps, {n_thr} threads over row blocks, {dt_mt:.3f} s per step")
+        # Direction of Table 3 on the CPU side (numpy forms of the two comparison methods next to the oracle's codec):
+        # signal-to-noise in dB at 32 values per group on a 256 K-element slice of the same payload
+        import oracle.quality as OQ
+        t3 = OQ.table(xs_host[0][:64 * 4096], group=32)
+        cpu["table3_direction_sqnr_db_g32"] = {f"int{b}": {k: round(v, 2) for k, v in row.items()} for b, row in t3.items()}
 
     out = {
         "metric": "effective HBM GB/s (and % of peak) for quantize_pack + reduce_requant, bits 2-8",

@@ -370,6 +370,33 @@ static_assert(pair_map_consistent<2>() && pair_map_consistent<3>() && pair_map_c
 // Every mask below is a literal of a two-operand `and` (see the note on instruction forms at the top), shifts go to
 // the right wherever a plain shift does, and the one wrap-around that is needed (element 0 of the 3-bit layout) is a
 // rotate.
+// The 16 bits of the 1-bit plane spread so that the bit of element e sits at 2e - 1, directly below the element's 2-bit
+// field of the 2-bit plane at 2e, 2e + 1 (element 0's bit wraps to bit 31).
+FCV2_HD uint32_t spread_extra_bits16(uint32_t p1) {
+    uint32_t x = and_lit<0x00FF00FFu>((p1 << 8) | p1);  // bit e -> 2e ...
+    x = and_lit<0x0F0F0F0Fu>((x << 4) | x);
+    x = and_lit<0x33333333u>((x << 2) | x);
+    x = and_lit<0x55555555u>((x << 1) | x);
+    return rotr32(x, 1);  // ... then turned right by one
+}
+
+// 3 bits: the pair registers from the 2-bit plane word and the spread extra bits S.
+FCV2_HD void codes_pairs16_b3(uint32_t p2, uint32_t S, uint32_t (&Q)[8]) {
+    // even elements: field at 4j, 4j + 1 from the plane, bit at 4j - 1 from S; odd elements: bit at 4j + 1 from S, field
+    // at 4j + 2, 4j + 3 from the plane.  One bit-select each, with the same mask.
+    const uint32_t M = vreg_const<0x33333333u>();
+    const uint32_t We = bit_select(M, p2, S), Wo = bit_select(M, S, p2);
+    const uint32_t We8 = rotr32(We, 8), Wo8 = Wo >> 8;  // elements 6, 8 / 14, 0 and 5, 7 / 13, 15 at the same four positions
+    Q[0] = and_lit<0x000E000Eu>(Wo);   // elements 1, 9    at bit 1
+    Q[1] = and_lit<0x00380038u>(We);   // elements 2, 10   at bit 3
+    Q[2] = and_lit<0x00E000E0u>(Wo);   // elements 3, 11   at bit 5
+    Q[3] = and_lit<0x03800380u>(We);   // elements 4, 12   at bit 7
+    Q[4] = and_lit<0x000E000Eu>(Wo8);  // elements 5, 13
+    Q[5] = and_lit<0x00380038u>(We8);  // elements 6, 14
+    Q[6] = and_lit<0x00E000E0u>(Wo8);  // elements 7, 15
+    Q[7] = and_lit<0x03800380u>(We8);  // elements 8, 0
+}
+
 template <int BITS> FCV2_HD void codes_pairs16(uint32_t p4a, uint32_t p4b, uint32_t p2, uint32_t p1, uint32_t (&Q)[8]) {
     if (BITS == 2) {
         const uint32_t B = p2 >> 10;  // element 5 at bit 0, element 13 at bit 16
@@ -382,26 +409,7 @@ template <int BITS> FCV2_HD void codes_pairs16(uint32_t p4a, uint32_t p4b, uint3
         Q[6] = and_lit<0x000C000Cu>(B);
         Q[7] = and_lit<0x00300030u>(B);
     } else if (BITS == 3) {
-        // extra bits spread to every second position (bit e -> 2e), then turned right by one: the bit of element e sits
-        // at 2e - 1, directly below the element's 2-bit field at 2e, 2e + 1 (element 0's bit wraps to bit 31)
-        uint32_t x = and_lit<0x00FF00FFu>((p1 << 8) | p1);
-        x = and_lit<0x0F0F0F0Fu>((x << 4) | x);
-        x = and_lit<0x33333333u>((x << 2) | x);
-        x = and_lit<0x55555555u>((x << 1) | x);
-        const uint32_t S = rotr32(x, 1);
-        // even elements: field at 4j, 4j + 1 from the plane, bit at 4j - 1 from S; odd elements: bit at 4j + 1 from S, field
-        // at 4j + 2, 4j + 3 from the plane.  One bit-select each, with the same mask.
-        const uint32_t M = vreg_const<0x33333333u>();
-        const uint32_t We = bit_select(M, p2, S), Wo = bit_select(M, S, p2);
-        const uint32_t We8 = rotr32(We, 8), Wo8 = Wo >> 8;  // elements 6, 8 / 14, 0 and 5, 7 / 13, 15 at the same four positions
-        Q[0] = and_lit<0x000E000Eu>(Wo);   // elements 1, 9    at bit 1
-        Q[1] = and_lit<0x00380038u>(We);   // elements 2, 10   at bit 3
-        Q[2] = and_lit<0x00E000E0u>(Wo);   // elements 3, 11   at bit 5
-        Q[3] = and_lit<0x03800380u>(We);   // elements 4, 12   at bit 7
-        Q[4] = and_lit<0x000E000Eu>(Wo8);  // elements 5, 13
-        Q[5] = and_lit<0x00380038u>(We8);  // elements 6, 14
-        Q[6] = and_lit<0x00E000E0u>(Wo8);  // elements 7, 15
-        Q[7] = and_lit<0x03800380u>(We8);  // elements 8, 0
+        codes_pairs16_b3(p2, spread_extra_bits16(p1), Q);
     } else {
         const uint32_t Ba = p4a >> 8, Bb = p4b >> 8;
         Q[0] = and_lit<0x000F000Fu>(p4a);

@@ -13,6 +13,12 @@
 #ifndef FCV2_REDUCE_WAVES32
 #define FCV2_REDUCE_WAVES32 4
 #endif
+#ifndef FCV2_REDUCE_WAVES16
+#define FCV2_REDUCE_WAVES16 6
+#endif
+#ifndef FCV2_REDUCE_CH
+#define FCV2_REDUCE_CH 2
+#endif
 #ifndef FCV2_REDUCE_PATCH
 #define FCV2_REDUCE_PATCH kPatchOverlay
 #endif
@@ -47,6 +53,9 @@ template <int BITS> struct UnitPairMap {  // codes_pairs on two units of 8: unit
     static constexpr int pos(int) { return 0; }
 };
 
+// (Measured and not used: taking the spread of the 3-bit format's extra bits from two 256-entry LDS tables instead of
+// computing it -- 12 VALU cycles instead of 35 per peer and 16 elements -- made the kernel 7 % slower: two more LDS
+// reads at scattered addresses per peer, in front of everything else the peer needs.)
 template <int BITS, int EPL, bool SR, int PATCH>
 __device__ __forceinline__ void add_peer_values(const RawPlanes<EPL>& r, const GroupMeta& m, uint32_t lig, uint4* row, float (&acc)[EPL]) {
     typedef _Float16 half2v __attribute__((ext_vector_type(2)));
@@ -162,14 +171,14 @@ template <int BITS, int EPL, int LPG, bool SR, int PATCH>
 // Peers are taken two at a time (both peers' loads issued before either is decoded).  Every peer in flight costs
 // about 15 registers; with two the kernel needs 65 to 74 and six or seven waves fit a SIMD, which measured faster
 // than four peers in flight at four or five waves, and faster than one peer at eight.
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(EPL == 32 ? FCV2_REDUCE_WAVES32 : 6)))
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(EPL == 32 ? FCV2_REDUCE_WAVES32 : FCV2_REDUCE_WAVES16)))
 void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
                                                            uint8_t* __restrict__ out, Rec rec_out, float* __restrict__ sum_out,
                                                            uint32_t meta_mode_in, uint32_t meta_mode_out) {
-    constexpr int CH = 2;  // peers in flight
+    constexpr int CH = FCV2_REDUCE_CH;  // peers in flight
     constexpr int ROW = 16 / 4 + 1;  // uint4 per private row of 16 dwords, one of padding: conflict-free 16-byte accesses
-    __shared__ uint4 lds[kBlock * ROW];
-    __shared__ float tabs[kScaleTables];
+    __shared__ uint4 lds[kBlock * ROW];  // 20 KiB: eight blocks fill the 160 KiB of a compute unit exactly
+    extern __shared__ float tabs[];      // the scale tables of the integer metadata: dynamic, present only when a format uses them
     if (meta_mode_in == kMetaInt || meta_mode_out == kMetaInt) fill_scale_tables(tabs);
     const uint32_t L = xcd_tile_block(blockIdx.x, gridDim.x) * kBlock + threadIdx.x;
     if (L >= n_lanes) return;
@@ -298,8 +307,9 @@ template <int BITS, int G, bool SR> struct LaunchReduce {
         constexpr int EPL = FCV2_REDUCE_EPL(G);
         constexpr int PATCH = FCV2_REDUCE_PATCH;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
-        return launch(k_reduce_requant<BITS, EPL, G / EPL, SR, PATCH>, dim3(grid_lanes_xcd(n_lanes)), dim3(kBlock), 0, st, peers, n_peers,
-                      n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
+        const size_t tab_bytes = (mf_in == kMetaInt || mf_out == kMetaInt) ? sizeof(float) * kScaleTables : 0;
+        return launch(k_reduce_requant<BITS, EPL, G / EPL, SR, PATCH>, dim3(grid_lanes_xcd(n_lanes)), dim3(kBlock), tab_bytes, st, peers,
+                      n_peers, n_lanes, rec_in, (uint8_t*)out, rec_out, sum_out, mf_in, mf_out);
     }
 };
 template <int BITS, int G, bool SR> struct LaunchReduceMixed {  // BITS = output width
