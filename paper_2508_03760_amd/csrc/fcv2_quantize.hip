@@ -42,21 +42,24 @@ __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restr
         }
     };
     // Two tiles are kept in flight per wave (two register sets, ping-pong, so loaded data is never moved); the
-    // refill of a set is issued right after the tile that used it has been stored.  Loads are unconditional
-    // (past the end they re-read the last tile): conditional ones would force full waits.
+    // refill of a set is issued right after the tile that used it has been stored.  Loads are unconditional:
+    // conditional ones would force full waits.  A refill past the wave's last tile asks for one 16-byte piece of the
+    // tensor's last tile in every lane (a single cache line per load instead of sixteen) and is never used.
     const uint32_t last = n_tiles - 1;
-    TileIn a = tile_load(x, (uint64_t)tile * 256, lane, n_pieces - tile * 256);
-    uint32_t t1 = min(tile + stride, last);
-    TileIn b = tile_load(x, (uint64_t)t1 * 256, lane, n_pieces - t1 * 256);
+    auto fetch = [&](uint32_t t) {
+        const bool real = t < n_tiles;
+        const uint32_t tt = real ? t : last;
+        return tile_load(x, (uint64_t)tt * 256, lane, real ? n_pieces - tt * 256 : 1u);
+    };
+    TileIn a = fetch(tile);
+    TileIn b = fetch(tile + stride);
     while (true) {
         process(a, tile);
-        uint32_t t2 = min(tile + 2 * stride, last);
-        a = tile_load(x, (uint64_t)t2 * 256, lane, n_pieces - t2 * 256);
+        a = fetch(tile + 2 * stride);
         tile += stride;
         if (tile >= n_tiles) break;
         process(b, tile);
-        t2 = min(tile + 2 * stride, last);
-        b = tile_load(x, (uint64_t)t2 * 256, lane, n_pieces - t2 * 256);
+        b = fetch(tile + 2 * stride);
         tile += stride;
         if (tile >= n_tiles) break;
     }
