@@ -20,7 +20,7 @@
 #define FCV2_REDUCE_CH 2
 #endif
 #ifndef FCV2_REDUCE_PATCH
-#define FCV2_REDUCE_PATCH kPatchOverlay
+#define FCV2_REDUCE_PATCH(BITS) ((BITS) <= 3 ? kPatchOverlay : kPatchPark)
 #endif
 
 namespace fcv2 {
@@ -74,24 +74,19 @@ __device__ __forceinline__ void add_peer_values(const RawPlanes<EPL>& r, const G
     float mult[9];
 #pragma unroll
     for (int q = 0; q < 9; ++q) mult[q] = s * __builtin_ldexpf(1.0f, 24 - q);  // only the positions in use survive
-    // The body exists twice: for scales below 2^100 (always, unless the data spans more than that: 2^24 * scale could
+    // Decoding exists twice: for scales below 2^100 (always, unless the data spans more than that: 2^24 * scale could
     // overflow) codes go into the mixed-precision FMA as fp16 denormals; otherwise they are converted one by one.
-    auto body = [&](auto fast_tag) {
-    constexpr bool fast = decltype(fast_tag)::value;
-#pragma unroll
-    for (int h = 0; h < EPL / 16; ++h) {
-        const uint32_t rmin = relmin - 16u * h, rmax = relmax - 16u * h;  // the same inside these 16 elements
-        if (SR && PATCH == kPatchOverlay) {
-            if (rmin < 16u) o[rmin] = smin ^ t;
-            if (rmax < 16u) o[rmax] = smax ^ t;
-        }
+    // codes16 prepares the 16 codes of half h in the form its kind of decoding takes, value decodes element e of them.
+    struct Codes16 {
         uint32_t Q[8];
         float qf[16];
-        if constexpr (fast) {
+    };
+    auto codes16 = [&](auto fast_tag, int h, Codes16& c) {
+        if constexpr (decltype(fast_tag)::value) {
             if constexpr (IN_PLACE) {
                 const uint32_t p1 = P::w1 ? (EPL == 16 ? r.p1 : (h == 0 ? and_lit<0xFFFFu>(r.p1) : r.p1 >> 16)) : 0u;
                 codes_pairs16<BITS>(P::w4 ? r.p4[(2 * h) % (EPL / 8)] : 0u, P::w4 ? r.p4[(2 * h + 1) % (EPL / 8)] : 0u,
-                                    P::w2 ? r.p2[h % ((EPL + 15) / 16)] : 0u, p1, Q);
+                                    P::w2 ? r.p2[h % ((EPL + 15) / 16)] : 0u, p1, c.Q);
             } else {
 #pragma unroll
                 for (int uu = 0; uu < 2; ++uu) {
@@ -102,7 +97,7 @@ __device__ __forceinline__ void add_peer_values(const RawPlanes<EPL>& r, const G
                     const uint32_t p1 = P::w1 ? ((r.p1 >> (8 * u)) & 0xFFu) : 0u;
                     codes_pairs<BITS>(P::w8 ? r.p8[2 * u] : 0u, P::w8 ? r.p8[2 * u + 1] : 0u, p4, p2, p1, Q4);
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) Q[4 * uu + k] = Q4[k];
+                    for (int k = 0; k < 4; ++k) c.Q[4 * uu + k] = Q4[k];
                 }
             }
         } else {
@@ -111,60 +106,84 @@ __device__ __forceinline__ void add_peer_values(const RawPlanes<EPL>& r, const G
                 float q8[8];
                 unit_codes<BITS, EPL>(r, 2 * h + uu, q8);
 #pragma unroll
-                for (int j = 0; j < 8; ++j) qf[8 * uu + j] = q8[j];
+                for (int j = 0; j < 8; ++j) c.qf[8 * uu + j] = q8[j];
             }
         }
-        auto value = [&](int e) -> float {  // element e of these 16, decoded
-            if constexpr (!fast) {
-                return __fmaf_rn(qf[e], s, lo);
-            } else {
-                const half2v hh = __builtin_bit_cast(half2v, Q[M::k_of(e)]);
-                return __builtin_fmaf(M::in_hi(e) ? (float)hh.y : (float)hh.x, mult[M::pos(M::k_of(e))], lo);
+    };
+    auto value = [&](auto fast_tag, const Codes16& c, int e) -> float {
+        if constexpr (!decltype(fast_tag)::value) {
+            return __fmaf_rn(c.qf[e], s, lo);
+        } else {
+            const half2v hh = __builtin_bit_cast(half2v, c.Q[M::k_of(e)]);
+            return __builtin_fmaf(M::in_hi(e) ? (float)hh.y : (float)hh.x, mult[M::pos(M::k_of(e))], lo);
+        }
+    };
+    if constexpr (SR && PATCH == kPatchOverlay) {
+        // everything of a peer inside one branch on the scale: the decoded values go straight into the accumulators, a
+        // quarter at a time, so that they are never all live at once
+        auto body = [&](auto fast_tag) {
+#pragma unroll
+            for (int h = 0; h < EPL / 16; ++h) {
+                const uint32_t rmin = relmin - 16u * h, rmax = relmax - 16u * h;  // the same inside these 16 elements
+                if (rmin < 16u) o[rmin] = smin ^ t;
+                if (rmax < 16u) o[rmax] = smax ^ t;
+                Codes16 c;
+                codes16(fast_tag, h, c);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {  // a wave's LDS operations execute in issue order: these reads see the writes above
+                    const uint4 x4 = row[i];
+                    const uint32_t x[4] = {x4.x, x4.y, x4.z, x4.w};
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int e = 4 * i + b;
+                        acc[16 * h + e] = __fadd_rn(acc[16 * h + e], u2f(f2u(value(fast_tag, c, e)) ^ x[b]));
+                    }
+                }
+                if (rmin < 16u) o[rmin] = 0u;  // ... and these zeros land after them
+                if (rmax < 16u) o[rmax] = 0u;
             }
         };
-        if (!SR) {
+        if (s < 0x1p+100f)
+            body(std::true_type{});
+        else
+            body(std::false_type{});
+    } else {
+        // only the decoding sits inside the branch on the scale; parking and accumulating follow it once
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[16 * h + e] = __fadd_rn(acc[16 * h + e], value(e));
-        } else if (PATCH == kPatchOverlay) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {  // a wave's LDS operations execute in issue order: these reads see the writes above
-                const uint4 x4 = row[i];
-                const uint32_t x[4] = {x4.x, x4.y, x4.z, x4.w};
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const int e = 4 * i + b;
-                    acc[16 * h + e] = __fadd_rn(acc[16 * h + e], u2f(f2u(value(e)) ^ x[b]));
-                }
-            }
-            if (rmin < 16u) o[rmin] = 0u;  // ... and these zeros land after them
-            if (rmax < 16u) o[rmax] = 0u;
-        } else {
+        for (int h = 0; h < EPL / 16; ++h) {
             float v[16];
+            if (s < 0x1p+100f) {
+                Codes16 c;
+                codes16(std::true_type{}, h, c);
 #pragma unroll
-            for (int e = 0; e < 16; ++e) v[e] = value(e);
-            if (rmin < 16u || rmax < 16u) {
+                for (int e = 0; e < 16; ++e) v[e] = value(std::true_type{}, c, e);
+            } else {
+                Codes16 c;
+                codes16(std::false_type{}, h, c);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) row[i] = make_uint4(f2u(v[4 * i]), f2u(v[4 * i + 1]), f2u(v[4 * i + 2]), f2u(v[4 * i + 3]));
-                if (rmin < 16u) o[rmin] = smin;
-                if (rmax < 16u) o[rmax] = smax;
+                for (int e = 0; e < 16; ++e) v[e] = value(std::false_type{}, c, e);
+            }
+            if (SR) {
+                const uint32_t rmin = relmin - 16u * h, rmax = relmax - 16u * h;
+                if (rmin < 16u || rmax < 16u) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint4 a = row[i];
-                    v[4 * i] = u2f(a.x);
-                    v[4 * i + 1] = u2f(a.y);
-                    v[4 * i + 2] = u2f(a.z);
-                    v[4 * i + 3] = u2f(a.w);
+                    for (int i = 0; i < 4; ++i) row[i] = make_uint4(f2u(v[4 * i]), f2u(v[4 * i + 1]), f2u(v[4 * i + 2]), f2u(v[4 * i + 3]));
+                    if (rmin < 16u) o[rmin] = smin;
+                    if (rmax < 16u) o[rmax] = smax;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const uint4 a = row[i];
+                        v[4 * i] = u2f(a.x);
+                        v[4 * i + 1] = u2f(a.y);
+                        v[4 * i + 2] = u2f(a.z);
+                        v[4 * i + 3] = u2f(a.w);
+                    }
                 }
             }
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[16 * h + e] = __fadd_rn(acc[16 * h + e], v[e]);
         }
     }
-    };
-    if (s < 0x1p+100f)
-        body(std::true_type{});
-    else
-        body(std::false_type{});
 }
 
 template <int BITS, int EPL, int LPG, bool SR, int PATCH>
@@ -305,7 +324,7 @@ template <int BITS, int G, bool SR> struct LaunchReduce {
     static int run(const PeerPtrs& peers, int n_peers, uint64_t n, const Rec& rec_in, void* out, const Rec& rec_out,
                    float* sum_out, uint32_t mf_in, uint32_t mf_out, hipStream_t st) {
         constexpr int EPL = FCV2_REDUCE_EPL(G);
-        constexpr int PATCH = FCV2_REDUCE_PATCH;
+        constexpr int PATCH = FCV2_REDUCE_PATCH(BITS);
         const uint32_t n_lanes = (uint32_t)(n / EPL);
         const size_t tab_bytes = (mf_in == kMetaInt || mf_out == kMetaInt) ? sizeof(float) * kScaleTables : 0;
         return launch(k_reduce_requant<BITS, EPL, G / EPL, SR, PATCH>, dim3(grid_lanes_xcd(n_lanes)), dim3(kBlock), tab_bytes, st, peers,
