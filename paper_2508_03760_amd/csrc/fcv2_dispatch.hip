@@ -212,8 +212,8 @@ __global__ __launch_bounds__(kChunk) void k_dispatch_dest(const int32_t* __restr
 // only, so a store instruction that writes "this wave's piece of a plane" starts and ends inside lines, and metadata
 // written by one lane in four touches a few bytes of each line.  The main kernel therefore assembles whole records in
 // LDS and copies each to its K destinations as one contiguous run whose store instructions cover 8 whole lines each,
-// with the non-temporal hint (measured on the MI355X, 65,536 copies: 2-bit rows of 2,352 bytes 83 -> 58 us for the whole
-// call, 8-bit rows of 7,728 bytes 174 -> 119 us).  The direct kernel below it serves the shapes whose records do not fit.
+// with the non-temporal hint (measured on the MI355X, 65,536 copies, this kernel alone: 2-bit rows of 2,352 bytes
+// 83 -> 58 us, 8-bit rows of 7,728 bytes 174 -> 119 us).  The direct kernel below it serves the shapes whose records do not fit.
 
 // Lane's share of a record, written at `o` (the record's first byte, LDS or global) through `ST`.
 template <int BITS, int LPG, bool SR, class ST>

@@ -1,12 +1,15 @@
 // fcv2_reduce.hip -- fcv2_reduce_requant: the local step of the two-step AllReduce (Sections 3.1, 3.4), kernels and launch.
 #include "fcv2_host.h"
 
-// Elements per lane, waves per SIMD at 32 elements per lane, and the way spikes are restored.  Measured on the MI355X on
-// the 16 M-element payload with 8 peers (us per launch at 2 / 3 / 8 bits, one run): 16 elements per lane with the
-// overlay 24.9 / 26.6 / 34.1, with the park 25.5 / 27.2 / 33.6; 32 elements per lane (112 registers, four waves per
-// SIMD) with the overlay 23.6 / 26.9 / 34.8, with the park 27.4 / 29.2 / 34.6; at five waves it spills.  The peer loop
-// costs the same per element either way (the FMA, the add and the unpacking are per element); what 32 elements per lane
-// save in per-lane work they lose in occupancy.
+// Elements per lane, waves per SIMD, peers in flight and the way spikes are restored, with what was measured on the
+// MI355X (16 M-element payload, 8 peers, inputs not in the last-level cache, us per launch, runs on one machine):
+//   at 2 / 3 / 4 / 5 / 6 / 7 / 8 bits, 16 elements per lane: overlay at 2 and 3 bits and park above (the choice below)
+//   26.2 / 28.3 / 27.7 / 32.2 / 32.5 / 38.3 / 34.1; park everywhere 26.6 / 28.2 / 27.7 / 32.3 / 32.4 / 38.2 / 34.1;
+//   32 elements per lane (112 registers, four waves per SIMD; five spill): within 1 us of 16 at every width, not better;
+//   one peer in flight at eight waves 29.7 at 3 bits, two at seven waves 28.5, the next two peers requested under the
+//   decoding of the current two 29.6 (against 28.8 in that run).
+// The peer loop costs the same per element either way (the FMA, the add and the unpacking are per element); what 32
+// elements per lane save in per-lane work they lose in occupancy.
 #ifndef FCV2_REDUCE_EPL
 #define FCV2_REDUCE_EPL(G) 16
 #endif
@@ -29,11 +32,10 @@ namespace fcv2 {
 //  - codes are unpacked into 16-bit halves and fed to v_fma_mix_f32 as fp16 denormals (q * 2^-24) against the
 //    scale pre-multiplied by 2^24: the product is the same real number q * scale, the FMA rounds once, so the
 //    result is bit-identical to fma(float(q), scale, lo) without a conversion instruction per element;
-//  - the spikes of every peer are put back through an overlay row in LDS (overlay_spikes below): a dynamic
-//    register index done by memory.
+//  - the spikes of every peer are put back through a private row in LDS: a dynamic register index done by memory.
 // Spike restoration (Section 3.3: after dequantization the two spikes of a group go back to their places).  A spike
 // position is a dynamic index into the lane's registers, which only memory can do; each lane has a private row of 16
-// dwords in LDS for it, and a lane's EPL elements are handled 16 at a time.  Two ways, chosen per kernel:
+// dwords in LDS for it, and a lane's EPL elements are handled 16 at a time.  Two ways, chosen per bit width:
 //   park:    a lane that owns a spike in these 16 elements writes its 16 decoded values to the row, overwrites the
 //            spike slot and reads the row back.  No extra arithmetic, 8 sixteen-byte LDS operations.
 //   overlay: the row is all zero between uses.  The wire format stores code 0 at a spike position, so what the decoder
