@@ -58,6 +58,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-sweep", action="store_true", help="skip the bit-width sweep and the dispatch workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--attribution", action="store_true",
+                    help="only launch reduce_requant over peer counts, with and without spike reserving, float and integer "
+                         "metadata, each case on a tensor size of its own (so a profiler's per-kernel, per-grid counters "
+                         "can be told apart), print the cases and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -83,6 +87,31 @@ def main():
 
     xs_host = [W.tensor(2, p).reshape(-1) for p in range(n_peers)]
     xs = [bf16(x) for x in xs_host]
+
+    if args.attribution:
+        # For rocprofv3 --pmc SQ_INSTS_VALU: the slope over the peer count is the cost of a peer, the intercept the
+        # requantization.  Case i runs on n - i * 262,144 elements, so every case has a grid size of its own.
+        import ctypes as C
+        lib = fcv2.lib()
+        stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        cases, i = [], 0
+        for label, bits, grp, flags in (("b3_g128_sr", 3, 128, SR), ("b3_g128_plain", 3, 128, 0), ("b3_g32_sr", 3, 32, SR),
+                                        ("b3_g32_sr_int_meta", 3, 32, SR | fcv2.F_META_INT), ("b2_g128_sr", 2, 128, SR),
+                                        ("b5_g128_sr", 5, 128, SR), ("b8_g128_sr", 8, 128, SR)):
+            for N in (1, 2, 4, 8, 16):
+                n_i = n - i * 262144
+                i += 1
+                peers = [fcv2.quantize_pack(xs[p % n_peers][:n_i], bits, grp, flags) for p in range(N)]
+                out = torch.zeros(fcv2.get_layout(n_i, bits, grp, flags).total_bytes, dtype=torch.uint8, device=dev)
+                fmt = fcv2._Fmt(bits, grp, flags)
+                arr = (C.c_void_p * N)(*[p.data_ptr() for p in peers])
+                for _ in range(3):
+                    rc = lib.fcv2_reduce_requant(arr, N, n_i, C.byref(fmt), C.byref(fmt), C.c_void_p(out.data_ptr()), None, stream)
+                    assert rc == 0, rc
+                torch.cuda.synchronize()
+                cases.append(dict(case=label, bits=bits, group=grp, peers=N, elements=n_i, lanes=n_i // 16))
+        print(json.dumps({"attribution_cases": cases}))
+        return
 
     def ev():
         return torch.cuda.Event(enable_timing=True)
