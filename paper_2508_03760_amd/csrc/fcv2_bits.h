@@ -120,10 +120,14 @@ template <int QMAX> FCV2_HD float div_by_qmax(float d) {
 // kPow10th[j + 1] = 2^(j/10) rounded to fp32 for j = -1..10.  kThr10th[j] = 2^((j - 1/2)/10) rounded UP to fp32 for
 // j = 0..10: a scale s has round(log2(s) * 10) >= 10e + j exactly when s >= 2^e * kThr10th[j] (the true thresholds
 // are irrational, so rounding them up to the next fp32 changes no decision).
-FCV2_TABLE float kPow10th[12] = {0x1.ddb680p-1f, 0x1.000000p+0f, 0x1.125fbep+0f, 0x1.261118p+0f, 0x1.3b2c48p+0f, 0x1.51cb46p+0f,
-                                 0x1.6a09e6p+0f, 0x1.840600p+0f, 0x1.9fdf8cp+0f, 0x1.bdb8cep+0f, 0x1.ddb680p+0f, 0x1.000000p+1f};
-FCV2_TABLE float kThr10th[11] = {0x1.ee8f36p-1f, 0x1.090720p+0f, 0x1.1c0cc0p+0f, 0x1.306fe2p+0f, 0x1.46499cp+0f, 0x1.5db4d2p+0f,
-                                 0x1.76ce52p+0f, 0x1.91b502p+0f, 0x1.ae89fap+0f, 0x1.cd70b4p+0f, 0x1.ee8f36p+0f};
+#define FCV2_POW10TH_VALUES                                                                                                    \
+    {0x1.ddb680p-1f, 0x1.000000p+0f, 0x1.125fbep+0f, 0x1.261118p+0f, 0x1.3b2c48p+0f, 0x1.51cb46p+0f,                               \
+     0x1.6a09e6p+0f, 0x1.840600p+0f, 0x1.9fdf8cp+0f, 0x1.bdb8cep+0f, 0x1.ddb680p+0f, 0x1.000000p+1f}
+#define FCV2_THR10TH_VALUES                                                                                                    \
+    {0x1.ee8f36p-1f, 0x1.090720p+0f, 0x1.1c0cc0p+0f, 0x1.306fe2p+0f, 0x1.46499cp+0f, 0x1.5db4d2p+0f,                               \
+     0x1.76ce52p+0f, 0x1.91b502p+0f, 0x1.ae89fap+0f, 0x1.cd70b4p+0f, 0x1.ee8f36p+0f}
+FCV2_TABLE float kPow10th[12] = FCV2_POW10TH_VALUES;
+FCV2_TABLE float kThr10th[11] = FCV2_THR10TH_VALUES;
 
 // k = 10e + j with 0 <= j <= 9, for -128 <= k <= 127.
 FCV2_D void split_tenths(int k, int& e, int& j) {
@@ -183,6 +187,32 @@ FCV2_D float scale_table_thr(int t) {
     return ldexpf(kThr10th[j], e);
 }
 constexpr int kScaleTablePow = 258, kScaleTableThr = 257;
+
+// Both tables written out at compile time, the power table first: what a kernel copies into LDS.  An entry is one of the
+// twelve (eleven) values above times an exact power of two between 2^-13 and 2^13, so the products are the values that
+// scale_table_pow and scale_table_thr compute (the host tests compare all of them).
+struct ScaleTables {
+    float v[kScaleTablePow + kScaleTableThr];
+};
+constexpr float exact_pow2(int e) {
+    float r = 1.0f;
+    for (; e > 0; --e) r *= 2.0f;
+    for (; e < 0; ++e) r *= 0.5f;
+    return r;
+}
+constexpr ScaleTables make_scale_tables() {
+    constexpr float pow10th[12] = FCV2_POW10TH_VALUES;
+    constexpr float thr10th[11] = FCV2_THR10TH_VALUES;
+    ScaleTables T{};
+    for (int t = 0; t < kScaleTablePow + kScaleTableThr; ++t) {
+        const bool is_pow = t < kScaleTablePow;
+        const int k = is_pow ? t - 129 : t - kScaleTablePow - 128;  // the code the entry belongs to
+        const int u = k + 130, q = (u * 205) >> 11, e = q - 13, j = u - 10 * q;  // split_tenths
+        T.v[t] = is_pow ? ((t >= 1 && t <= 256) ? pow10th[j + 1] * exact_pow2(e) : 0.0f) : thr10th[j] * exact_pow2(e);
+    }
+    return T;
+}
+FCV2_TABLE ScaleTables kScaleTablesInit = make_scale_tables();
 
 FCV2_D ScaleInt scale_int_from_tables(float s, const float* pow_tab, const float* thr_tab) {
     const int k0 = (s > 0.0f) ? scale_int_estimate(s) : -128;

@@ -54,11 +54,14 @@ constexpr uint32_t kMetaBf16 = 0, kMetaFp32 = 1, kMetaInt = 2;
 // them leaves the kernel; tabs holds kScaleTablePow + kScaleTableThr floats.
 constexpr int kScaleTables = kScaleTablePow + kScaleTableThr;
 __device__ __forceinline__ void fill_scale_tables(float* tabs) {
+    // a plain copy of the compile-time tables (515 floats): coalesced loads that depend on nothing, no arithmetic.
+    // (Issuing a kernel's first tile loads before this copy, so that its latency runs under theirs, measured no faster.)
     const int t = (int)threadIdx.x;
-    tabs[t] = scale_table_pow(t);
-    tabs[kScaleTablePow + t] = scale_table_thr(t);
-    if (t < kScaleTablePow - 256) tabs[256 + t] = scale_table_pow(256 + t);
-    if (t < kScaleTableThr - 256) tabs[kScaleTablePow + 256 + t] = scale_table_thr(256 + t);
+    const float a = kScaleTablesInit.v[t], b = kScaleTablesInit.v[256 + t];
+    const float c = kScaleTablesInit.v[t < kScaleTables - 512 ? 512 + t : 512];
+    tabs[t] = a;
+    tabs[256 + t] = b;
+    if (t < kScaleTables - 512) tabs[512 + t] = c;
     __syncthreads();
 }
 

@@ -368,8 +368,7 @@ __global__ __launch_bounds__(kRowsBlockMax) void k_dispatch_rows_t(const uint4* 
     // the padding between a record's sections travels with the copies: it is written as zero
     for (uint32_t i = threadIdx.x; i < rows_here * row_pieces; i += blockDim.x) recs[i] = make_uint4(0, 0, 0, 0);
     if (INT_META) {
-        for (uint32_t t = threadIdx.x; t < (uint32_t)kScaleTablePow; t += blockDim.x) tabs[t] = scale_table_pow((int)t);
-        for (uint32_t t = threadIdx.x; t < (uint32_t)kScaleTableThr; t += blockDim.x) tabs[kScaleTablePow + t] = scale_table_thr((int)t);
+        for (uint32_t t = threadIdx.x; t < (uint32_t)kScaleTables; t += blockDim.x) tabs[t] = kScaleTablesInit.v[t];
     }
     __syncthreads();
     int32_t my_before = 0, my_rank = 0;

@@ -126,11 +126,19 @@ void hc_scale_int_of(uint32_t first_bits, uint32_t count, int8_t* k, uint32_t* s
         memcpy(&s_bits[i], &r.s, 4);
     }
 }
+// Entries of the compile-time tables that differ (as bit patterns) from what the table functions compute.
+int hc_scale_tables_mismatches() {
+    int bad = 0;
+    for (int t = 0; t < kScaleTablePow + kScaleTableThr; ++t) {
+        const float want = t < kScaleTablePow ? scale_table_pow(t) : scale_table_thr(t - kScaleTablePow);
+        bad += memcmp(&want, &kScaleTablesInit.v[t], 4) != 0;
+    }
+    return bad;
+}
 // The same through the per-code tables.
 void hc_scale_int_from_tables(uint32_t first_bits, uint32_t count, int8_t* k, uint32_t* s_bits) {
-    static float pow_tab[kScaleTablePow], thr_tab[kScaleTableThr];
-    for (int t = 0; t < kScaleTablePow; ++t) pow_tab[t] = scale_table_pow(t);
-    for (int t = 0; t < kScaleTableThr; ++t) thr_tab[t] = scale_table_thr(t);
+    const float* pow_tab = kScaleTablesInit.v;  // the compile-time tables, as the kernels copy them into LDS
+    const float* thr_tab = kScaleTablesInit.v + kScaleTablePow;
     for (uint32_t i = 0; i < count; ++i) {
         const uint32_t b = first_bits + i;
         float f;

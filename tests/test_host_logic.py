@@ -37,6 +37,8 @@ def hc():
     L.hc_scale_int_of.argtypes = [C.c_uint32, C.c_uint32, C.POINTER(C.c_int8), C.POINTER(C.c_uint32)]
     L.hc_scale_int_from_tables.restype = None
     L.hc_scale_int_from_tables.argtypes = L.hc_scale_int_of.argtypes
+    L.hc_scale_tables_mismatches.restype = C.c_int
+    L.hc_scale_tables_mismatches.argtypes = []
     L.hc_scale_int_estimate.restype = C.c_int
     L.hc_scale_int_estimate.argtypes = [C.c_float]
     L.hc_scale_of_int.restype = C.c_float
@@ -230,6 +232,12 @@ def test_scale_int_every_significand(hc, exponent):
     assert np.array_equal(s, np.exp2(k.astype(np.float64) / 10.0).astype(np.float32))
     k2, s2 = _scale_int_block(hc, first, 1 << 23, tables=True)  # the table form the kernels keep in LDS
     assert np.array_equal(k, k2) and np.array_equal(s, s2)
+
+
+def test_compile_time_scale_tables_are_the_table_functions(hc):
+    """The 515 floats the kernels copy into LDS are written out at compile time (a table entry times an exact power of
+    two); each must be bit for bit what the table functions compute with ldexpf."""
+    assert hc.hc_scale_tables_mismatches() == 0
 
 
 def test_scale_int_estimate_is_within_one(hc):
