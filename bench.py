@@ -260,7 +260,7 @@ def main():
     torch.cuda.empty_cache()
 
     # ---- sweep over bit widths, and the dispatch workload -----------------------------------------------------
-    sweep, dispatch = {}, None
+    sweep, dispatch, mixed_width = {}, None, None
     if not args.no_sweep:
         for b in (2, 3, 4, 5, 6, 7, 8):
             s = make_sets(b, n_sets_for(b))
@@ -270,6 +270,17 @@ def main():
             sweep[str(b)] = {k: dict(us=round(k_b[k] * 1e3, 2), gbs=round(abb[k] / (k_b[k] * 1e-3) / 1e9, 1),
                                      frac=round(abb[k] / (k_b[k] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)) for k in abb}
             sweep[str(b)]["step_gbs"] = round(sum(abb[k] for k in STEP) / (ms_b * 1e-3) / 1e9, 1)
+            if b == 4:
+                # peers at 4 bits, output at 3: the width-changing form of the call (a separate, simpler kernel)
+                import ctypes as C
+                f_in, f_out = fcv2._Fmt(4, group, SR), fcv2._Fmt(3, group, SR)
+                st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+                ms_m = timed(lambda i: fcv2.lib().fcv2_reduce_requant(s[i % len(s)]["keep"][0], n_peers, n, C.byref(f_in), C.byref(f_out),
+                                                                      C.c_void_p(s[i % len(s)]["r"].data_ptr()), None, st),
+                             max(10, args.steps // 2), 3)
+                mixed_bytes = n_peers * packed_bytes(n, 4, group) + packed_bytes(n, 3, group)
+                mixed_width = dict(bits_in=4, bits_out=3, us=round(ms_m * 1e3, 2), algorithmic_bytes=mixed_bytes,
+                                   gbs=round(mixed_bytes / (ms_m * 1e-3) / 1e9, 1))
             del s
             torch.cuda.empty_cache()
         w3 = W.WORKLOADS[3]
@@ -580,7 +591,7 @@ def main():
         "warm_cache_gbs": round(total_bytes / (ms_warm * 1e-3) / 1e9, 1),  # the same two-call step on one buffer set
         "copy_ceiling_gbs": round(copy_gbs, 1), "copy_same_size_as_quantize_pack": copy_same_size,
         "three_call_step": three,
-        "kernels": kernels, "roofline": roofline, "alu_roofline": alu_roofline, "cpu_baseline": cpu, "sweep_bits": sweep, "dispatch": dispatch,
+        "kernels": kernels, "roofline": roofline, "alu_roofline": alu_roofline, "cpu_baseline": cpu, "sweep_bits": sweep, "reduce_requant_4bit_in_3bit_out": mixed_width, "dispatch": dispatch,
         "quality_proxy_sqnr": quality, "low_bit_default_shape_g32": low_bit, "two_step_allreduce_rank_share": two_step, "micro_chunk_pipelining": pipelined, "decode_latency_64x7168": latency, "large_allreduce_8192x8192_N8": large,
     }
     print(json.dumps(out))

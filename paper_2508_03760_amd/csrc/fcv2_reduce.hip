@@ -264,8 +264,8 @@ void k_reduce_requant(PeerPtrs peers, int n_peers, uint32_t n_lanes, Rec rec_in,
 }
 
 // The same step when the peers' bit width differs from the output's: the input width is a run-time value
-// (one uniform switch per peer), the output width stays a template parameter.  Not pipelined; a compatibility
-// path next to the specialised kernel above.
+// (one uniform switch around the peer loop), the output width stays a template parameter.  A compatibility path next to
+// the specialised kernel above: spikes always through the park, no choice of occupancy per width.
 template <int BITS_OUT, int EPL, int LPG, bool SR>
 __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers, int n_peers, uint32_t bits_in, uint32_t n_lanes,
                                                                  Rec rec_in, uint8_t* __restrict__ out, Rec rec_out,
@@ -283,29 +283,38 @@ __global__ __launch_bounds__(kBlock) void k_reduce_requant_mixed(PeerPtrs peers,
     float acc[EPL];
 #pragma unroll
     for (int j = 0; j < EPL; ++j) acc[j] = -0.0f;
-    for (int p = 0; p < n_peers; ++p) {
-        const BufferSrc src = buffer_src(peers.base[p], rec_in.total);
-        const uint32_t mraw = ld32(src, mo.at);
-        const uint32_t mraw2 = (LPG < 4 && SR) ? ld32(src, mo.at2) : 0u;
-        const GroupMeta m = (meta_mode_in == kMetaInt) ? spread_meta<LPG, SR, true>(mraw, mraw2, mo, tabs, rec_in.idx_bf16)
-                                                       : spread_meta<LPG, SR, false>(mraw, mraw2, mo, tabs, rec_in.idx_bf16);
-        switch (bits_in) {
-#define FCV2_CASE(B)                                                      \
-    case B: {                                                             \
-        const RawPlanes<EPL> r = load_planes<B, EPL>(src, rec_in, L);     \
-        add_peer_values<B, EPL, SR, kPatchPark>(r, m, lig, row, acc);     \
-        break;                                                            \
-    }
-            FCV2_CASE(2)
-            FCV2_CASE(3)
-            FCV2_CASE(4)
-            FCV2_CASE(5)
-            FCV2_CASE(6)
-            FCV2_CASE(7)
-            default:
-                FCV2_CASE(8)
-#undef FCV2_CASE
+    // One uniform switch on the input width around the whole peer loop; inside it peers are taken two at a time, both
+    // peers' loads issued before either is decoded (an odd last peer is requested twice and added once).
+    auto sum_peers = [&](auto bits_tag) {
+        constexpr int B = decltype(bits_tag)::value;
+        auto add_peer = [&](const RawPlanes<EPL>& r, uint32_t mraw, uint32_t mraw2) {
+            const GroupMeta m = (meta_mode_in == kMetaInt) ? spread_meta<LPG, SR, true>(mraw, mraw2, mo, tabs, rec_in.idx_bf16)
+                                                           : spread_meta<LPG, SR, false>(mraw, mraw2, mo, tabs, rec_in.idx_bf16);
+            add_peer_values<B, EPL, SR, kPatchPark>(r, m, lig, row, acc);
+        };
+        for (int p = 0; p < n_peers; p += 2) {
+            const bool two = p + 1 < n_peers;
+            RawPlanes<EPL> r[2];
+            uint32_t mraw[2], mraw2[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const BufferSrc src = buffer_src(peers.base[(i == 1 && two) ? p + 1 : p], rec_in.total);
+                r[i] = load_planes<B, EPL>(src, rec_in, L);
+                mraw[i] = ld32(src, mo.at);
+                mraw2[i] = (LPG < 4 && SR) ? ld32(src, mo.at2) : 0u;
+            }
+            add_peer(r[0], mraw[0], mraw2[0]);
+            if (two) add_peer(r[1], mraw[1], mraw2[1]);
         }
+    };
+    switch (bits_in) {
+        case 2: sum_peers(std::integral_constant<int, 2>{}); break;
+        case 3: sum_peers(std::integral_constant<int, 3>{}); break;
+        case 4: sum_peers(std::integral_constant<int, 4>{}); break;
+        case 5: sum_peers(std::integral_constant<int, 5>{}); break;
+        case 6: sum_peers(std::integral_constant<int, 6>{}); break;
+        case 7: sum_peers(std::integral_constant<int, 7>{}); break;
+        default: sum_peers(std::integral_constant<int, 8>{}); break;
     }
     if (sum_out) {
         float4* dst = reinterpret_cast<float4*>(sum_out) + (EPL / 4) * (uint64_t)L;
