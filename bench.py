@@ -226,14 +226,15 @@ def main():
     roofline = dict(bound="hbm", kernel=kname, achieved=kernels[dom]["gbs"], peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(kernels[dom]["gbs"] / HBM_PEAK_GBS, 4), traffic=traffic, traffic_source=traffic_source,
                     algorithmic_bytes=ab[dom], us_per_launch=kernels[dom]["us"])
-    # What limits it in practice is VALU issue; the same launch against that bound, for context.  executed = VALU
-    # instructions per output element from the same rocprofv3 summary (SQ_INSTS_VALU); peak = 256 CU x 4 SIMD x 16 lanes x
-    # 2.4 GHz, no packed fp32.
+    # What limits it in practice is VALU time; the executed instruction rate of the same launch, for context (not a
+    # roofline: the nominal rate of 256 CU x 4 SIMD x 16 lanes x 2.4 GHz assumes 4 cycles per wave-wide instruction, and the
+    # two-operand forms this kernel mostly uses occupy a SIMD for 2.4, so the executed rate can exceed it).  executed = VALU
+    # instructions per output element from the same rocprofv3 summary (SQ_INSTS_VALU).
     alu_roofline = None
     if pk.get("valu_per_element") is not None:
         ops_s = pk["valu_per_element"] * n / (kern_ms[dom] * 1e-3) / 1e12
-        alu_roofline = dict(bound="alu", kernel=kname, achieved=round(ops_s, 2), peak=round(ALU_PEAK_TLOPS, 2), unit="T lane-op/s",
-                            frac=round(ops_s / ALU_PEAK_TLOPS, 4), executed_ops_per_element=pk["valu_per_element"],
+        alu_roofline = dict(kernel=kname, executed_ops_per_element=pk["valu_per_element"], executed_rate=round(ops_s, 2),
+                            nominal_rate_at_4_cycles_per_instruction=round(ALU_PEAK_TLOPS, 2), unit="T lane-op/s",
                             source="profiles/headline_step_b3_g128_n8.md (SQ_INSTS_VALU x 64 lanes / elements)")
     # practical streaming ceiling: the library's plain copy kernel on 1 GiB (source and destination together are eight
     # times the 256 MB last-level cache, so this is an HBM figure)
