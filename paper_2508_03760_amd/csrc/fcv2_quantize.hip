@@ -65,19 +65,32 @@ __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restr
     }
 }
 
-// Number of blocks of a persistent launch.  A compute unit holds 8 blocks of the quantize kernel (64 registers per
-// lane, 20 KiB of LDS per block).  A tensor of at most that many tiles gets one wave per tile, all resident at once;
-// a larger one gets 4 blocks per compute unit, each wave walking several tiles with the next loads in flight.
-// The compute-unit count is asked of the current device at every call (a cheap attribute read): nothing is cached, so a
-// process that moves between devices, or calls from several threads, always gets the count of the device it launches on.
-static unsigned persistent_grid(uint32_t n_tiles) {
+// Launch shape.  A compute unit holds 8 blocks of the quantize kernel (64 registers per lane, 22 KiB of LDS per block).
+// A tensor of at most that many tiles gets one wave per tile; a larger one gets 4 blocks per compute unit, each wave
+// walking several tiles with the next loads in flight.  In the first case the waves of a launch form a single
+// generation (all load, then all compute, then all store); from 4 bits up, where a record is a larger part of the
+// traffic, it measured 2 to 6 % faster on the 16 M-element tensor to let only 4 blocks into a compute unit at a time, so
+// that the later blocks' loads run under the earlier blocks' stores (3 and 5 to 7 blocks: slower; at 2 and 3 bits all 8
+// are faster).  The limit is set with unused dynamic LDS.  The compute-unit count is asked of the current device at
+// every call (a cheap attribute read): nothing is cached, so a process that moves between devices, or calls from
+// several threads, always gets the count of the device it launches on.
+struct QuantizeLaunch {
+    unsigned blocks;
+    size_t lds_pad;
+};
+static QuantizeLaunch quantize_launch_shape(uint32_t n_tiles, int bits) {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
         cus = 256;
     const unsigned need = (n_tiles + kWaves - 1) / kWaves;
-    const unsigned per_cu = need <= 8u * (unsigned)cus ? 8u : 4u;
-    const unsigned blocks = per_cu * (unsigned)cus;
-    return need < blocks ? need : blocks;
+    const bool one_tile_per_wave = need <= 8u * (unsigned)cus;
+    const unsigned blocks = (one_tile_per_wave ? 8u : 4u) * (unsigned)cus;
+    QuantizeLaunch q;
+    q.blocks = need < blocks ? need : blocks;
+    // 160 KiB of LDS per compute unit: blocks of 36 KiB fit four times, not five, whatever the allocation granule
+    constexpr size_t kStatic = sizeof(uint4) * kWaves * 64 * kRowU4 + sizeof(float) * kScaleTables;
+    q.lds_pad = (one_tile_per_wave && bits >= 4 && need > 4u * (unsigned)cus) ? (size_t)36864 - kStatic : 0;
+    return q;
 }
 
 template <int BITS, int G, bool SR> struct LaunchQuantize {
@@ -86,10 +99,11 @@ template <int BITS, int G, bool SR> struct LaunchQuantize {
         constexpr int EPL = kEplStream;
         const uint32_t n_lanes = (uint32_t)(n / EPL);
         const uint32_t n_tiles = (n_lanes + 63) / 64;
+        const QuantizeLaunch q = quantize_launch_shape(n_tiles, BITS);
         if (meta_mode == kMetaInt)
-            return launch(k_quantize_pack_t<BITS, G / EPL, SR, true>, dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
+            return launch(k_quantize_pack_t<BITS, G / EPL, SR, true>, dim3(q.blocks), dim3(kBlock), q.lds_pad, st,
                           (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_mode, n_lanes / n_slices, record_stride);
-        return launch(k_quantize_pack_t<BITS, G / EPL, SR, false>, dim3(persistent_grid(n_tiles)), dim3(kBlock), 0, st,
+        return launch(k_quantize_pack_t<BITS, G / EPL, SR, false>, dim3(q.blocks), dim3(kBlock), q.lds_pad, st,
                       (const uint4*)x, n_lanes, (uint8_t*)out, rec, meta_mode, n_lanes / n_slices, record_stride);
     }
 };
