@@ -233,7 +233,7 @@ FCV2_D ScaleInt scale_int_from_tables(float s, const float* pow_tab, const float
 // destination rows, the E expert starts (+ 8 words for the block scan) and, for integer metadata, the scale tables;
 // 64 KiB at most.  Among the row counts 1..64 that fit, the one with the smallest share of idle lanes wins (the first
 // such).  rows = 0: the shape does not fit the kernel.
-constexpr uint32_t kWaveScratchBytes = 5120, kRowsPlanThreadsMax = 512;
+constexpr uint32_t kWaveScratchBytes = 4096, kRowsPlanThreadsMax = 512;
 struct RowsPlan {
     uint32_t rows, threads;
     size_t lds_bytes;

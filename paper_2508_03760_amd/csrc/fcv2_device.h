@@ -633,9 +633,12 @@ __device__ __forceinline__ void wave_lds_sync() {
 }
 
 // A wave's tile of 64 x 32 consecutive bf16 (4 KiB) is fetched with fully coalesced 16-byte loads (piece P = k*64 + lane)
-// and turned, through LDS, into 32 consecutive elements per lane.  Rows of 64 bytes are padded to 80 so that the
-// 16-byte reads of 16 neighbouring lanes fall into different banks.
-constexpr int kRowU4 = 5;  // uint4 per lane row: 4 of data + 1 of padding
+// and turned, through LDS, into 32 consecutive elements per lane.  A lane's row is 64 bytes, four 16-byte slots, with
+// no padding: slot q of row r lives at position q ^ ((r >> 1) & 3), so that the 16-byte reads of eight neighbouring
+// lanes (two row parities x four slot positions) fall into eight different bank groups, and the writes of eight
+// neighbouring lanes still cover two whole rows.  4 KiB per wave.
+constexpr int kRowU4 = 4;  // uint4 per lane row
+__device__ __forceinline__ uint32_t tile_slot(uint32_t row, uint32_t q) { return row * kRowU4 + (q ^ ((row >> 1) & 3u)); }
 
 struct TileIn {
     uint4 piece[4];
@@ -657,12 +660,12 @@ __device__ __forceinline__ void tile_transpose(const TileIn& t, uint4* wave_lds,
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const uint32_t P = k * 64 + lane;
-        wave_lds[(P >> 2) * kRowU4 + (P & 3)] = t.piece[k];
+        wave_lds[tile_slot(P >> 2, P & 3)] = t.piece[k];
     }
     wave_lds_sync();
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        const uint4 v = wave_lds[lane * kRowU4 + k];
+        const uint4 v = wave_lds[tile_slot(lane, k)];
         w[4 * k] = v.x;
         w[4 * k + 1] = v.y;
         w[4 * k + 2] = v.z;

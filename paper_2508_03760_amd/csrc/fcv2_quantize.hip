@@ -42,8 +42,8 @@ __global__ __launch_bounds__(kBlock) void k_quantize_pack_t(const uint4* __restr
     }
 }
 
-// Launch shape: one block per four tiles.  A compute unit holds 8 blocks of the kernel (64 registers per lane, 22 KiB of
-// LDS per block), and at 2 to 7 bits that is the fastest at every size measured (16 M, 32 M, 64 M elements).  At 8 bits,
+// Launch shape: one block per four tiles.  A compute unit holds 8 blocks of the kernel (32 to 65 registers per lane, 16 to
+// 18 KiB of LDS per block), and at 2 to 7 bits that is the fastest at every size measured (16 M, 32 M, 64 M elements).  At 8 bits,
 // where the record is a third of the traffic, tensors of more blocks than the chip holds at once ran 6 % (32 M) and
 // 10 % (64 M) faster with only 4 blocks in a compute unit at a time: later blocks' loads then run under earlier blocks'
 // stores.  The limit is set with unused dynamic LDS.  The compute-unit count is asked of the current device at every call

@@ -10,7 +10,7 @@ template <int BITS, int LPG, bool SR, bool OUT_FP32>
 __global__ __launch_bounds__(kBlock) void k_unpack_dequant_t(PeerPtrs records, uint32_t slice_lanes, Rec rec, uint32_t n_lanes,
                                                              uint4* __restrict__ out, uint32_t meta_mode) {
     constexpr int EPL = kEplStream;
-    constexpr int ROW = OUT_FP32 ? 9 : kRowU4;  // uint4 per lane row incl. one of padding
+    constexpr int ROW = OUT_FP32 ? 9 : 5;  // uint4 per lane row incl. one of padding
     constexpr int NP = OUT_FP32 ? 8 : 4;       // 16-byte pieces per lane
     __shared__ uint4 lds[kWaves][64 * ROW];
     const uint32_t lane = threadIdx.x & 63, wave = threadIdx.x >> 6;

@@ -280,14 +280,14 @@ def test_dispatch_launch_plan(hc):
     starts = (256 + 8) * 4  # the block's copy of the expert starts, and the words its scan needs
 
     # the DeepSeek-V3-shaped workload: H = 7168 = 224 lanes, 2-bit rows of 2,352 bytes, 8 copies: two tokens fill 7 waves
-    assert plan(224, 8, 2352) == (2, 448, 7 * 5120 + 2 * 2352 + 2 * 8 * 4 + starts)
-    assert plan(256, 8, 2688) == (1, 256, 4 * 5120 + 2688 + 32 + starts)  # H = 8192: one token is four whole waves
+    assert plan(224, 8, 2352) == (2, 448, 7 * 4096 + 2 * 2352 + 2 * 8 * 4 + starts)
+    assert plan(256, 8, 2688) == (1, 256, 4 * 4096 + 2688 + 32 + starts)  # H = 8192: one token is four whole waves
     assert plan(128, 8, 1344)[:2] == (1, 128)                         # H = 4096: the first count without idle lanes
     assert plan(1, 2, 32)[:2] == (64, 64)                             # H = 32: 64 tokens share a wave
     assert plan(513, 8, 5000) == (0, 0, 0)                            # more than 512 lanes per token
-    assert plan(512, 8, 8 * 5120 + 30000) == (0, 0, 0)                # record too large for the LDS
-    assert plan(224, 8, 2256, 1) == (2, 448, 7 * 5120 + 2 * 2256 + 64 + starts + (258 + 257) * 4)
-    assert plan(224, 8, 2352, 0, 2048)[2] == 7 * 5120 + 2 * 2352 + 64 + (2048 + 8) * 4   # the most experts a call takes
+    assert plan(512, 8, 8 * 4096 + 30000) == (0, 0, 0)                # record too large for the LDS
+    assert plan(224, 8, 2256, 1) == (2, 448, 7 * 4096 + 2 * 2256 + 64 + starts + (258 + 257) * 4)
+    assert plan(224, 8, 2352, 0, 2048)[2] == 7 * 4096 + 2 * 2352 + 64 + (2048 + 8) * 4   # the most experts a call takes
     for lpr in list(range(1, 70)) + [96, 160, 224, 300, 448, 512]:
         for K in (1, 8, 33):
             for row_bytes in (16 * lpr, 40 * lpr + 48):
