@@ -239,7 +239,12 @@ struct RowsPlan {
     size_t lds_bytes;
 };
 static inline RowsPlan rows_plan(uint32_t lpr, uint32_t K, uint32_t row_bytes, bool int_meta, uint32_t E) {
-    RowsPlan best = {0, 0, 0};
+    // Candidates: R rows per block, as many whole waves as they need.  First choice: the count with the fewest idle lanes
+    // (the smallest such count).  If that block is larger than four waves and a smaller count fills at least four waves
+    // with at most an eighth of their lanes idle, the smallest such count is taken instead: smaller blocks finish their
+    // load - quantize - copy sequence sooner (measured on 7168-element rows: one row in four waves, 32 lanes idle,
+    // 62.3 us for the call, against two rows in seven full waves, 64.4 us).
+    RowsPlan best = {0, 0, 0}, small = {0, 0, 0};
     uint32_t best_idle = ~0u;
     for (uint32_t R = 1; R <= 64 && R * lpr <= kRowsPlanThreadsMax; ++R) {
         const uint32_t waves = (R * lpr + 63) / 64;
@@ -251,7 +256,9 @@ static inline RowsPlan rows_plan(uint32_t lpr, uint32_t K, uint32_t row_bytes, b
             best_idle = idle;
             best = {R, waves * 64, lds};
         }
+        if (small.rows == 0 && waves >= 4 && idle <= 128) small = {R, waves * 64, lds};
     }
+    if (best.threads > 4 * 64 && small.rows != 0 && small.rows < best.rows) return small;
     return best;
 }
 

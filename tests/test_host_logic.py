@@ -279,27 +279,37 @@ def test_dispatch_launch_plan(hc):
 
     starts = (256 + 8) * 4  # the block's copy of the expert starts, and the words its scan needs
 
-    # the DeepSeek-V3-shaped workload: H = 7168 = 224 lanes, 2-bit rows of 2,352 bytes, 8 copies: two tokens fill 7 waves
-    assert plan(224, 8, 2352) == (2, 448, 7 * 4096 + 2 * 2352 + 2 * 8 * 4 + starts)
+    # the DeepSeek-V3-shaped workload: H = 7168 = 224 lanes, 2-bit rows of 2,352 bytes, 8 copies: two tokens would fill 7
+    # waves exactly, but one token in four waves (an eighth of the lanes idle) is the smaller block, and it is taken
+    assert plan(224, 8, 2352) == (1, 256, 4 * 4096 + 2352 + 8 * 4 + starts)
     assert plan(256, 8, 2688) == (1, 256, 4 * 4096 + 2688 + 32 + starts)  # H = 8192: one token is four whole waves
     assert plan(128, 8, 1344)[:2] == (1, 128)                         # H = 4096: the first count without idle lanes
+    assert plan(160, 8, 1680)[:2] == (2, 320)                         # H = 5120: one token would leave a sixth of three waves idle
     assert plan(1, 2, 32)[:2] == (64, 64)                             # H = 32: 64 tokens share a wave
     assert plan(513, 8, 5000) == (0, 0, 0)                            # more than 512 lanes per token
     assert plan(512, 8, 8 * 4096 + 30000) == (0, 0, 0)                # record too large for the LDS
-    assert plan(224, 8, 2256, 1) == (2, 448, 7 * 4096 + 2 * 2256 + 64 + starts + (258 + 257) * 4)
-    assert plan(224, 8, 2352, 0, 2048)[2] == 7 * 4096 + 2 * 2352 + 64 + (2048 + 8) * 4   # the most experts a call takes
+    assert plan(224, 8, 2256, 1) == (1, 256, 4 * 4096 + 2256 + 32 + starts + (258 + 257) * 4)
+    assert plan(224, 8, 2352, 0, 2048)[2] == 4 * 4096 + 2352 + 32 + (2048 + 8) * 4   # the most experts a call takes
     for lpr in list(range(1, 70)) + [96, 160, 224, 300, 448, 512]:
         for K in (1, 8, 33):
             for row_bytes in (16 * lpr, 40 * lpr + 48):
                 rows, threads, lds = plan(lpr, K, row_bytes)
                 assert rows >= 1 and threads % 64 == 0 and 64 <= threads <= 512
                 assert rows * lpr <= threads < rows * lpr + 64 and lds <= 65536
-                # no smaller count has as few idle lanes
-                idle = (threads - rows * lpr) * 1024 // threads
-                for r in range(1, rows):
+                # the rule, stated once more: fewest idle lanes (smallest such count), unless that block is larger than four
+                # waves and a smaller count fills at least four waves with at most an eighth of the lanes idle
+                cands = []
+                for r in range(1, 65):
+                    if r * lpr > 512:
+                        break
                     w = -(-r * lpr // 64)
-                    assert (w * 64 - r * lpr) * 1024 // (w * 64) > idle
-
+                    if w * 4096 + r * row_bytes + r * K * 4 + starts > 65536:
+                        break
+                    cands.append((r, w, (w * 64 - r * lpr) * 1024 // (w * 64)))
+                best = min(cands, key=lambda c: (c[2], c[0]))
+                small = next((c for c in cands if c[1] >= 4 and c[2] <= 128), None)
+                want = small if (best[1] > 4 and small and small[0] < best[0]) else best
+                assert (rows, threads) == (want[0], want[1] * 64)
 
 
 def test_bench_reads_its_counters_from_the_committed_profile():
