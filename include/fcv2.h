@@ -123,7 +123,8 @@ int fcv2_unpack_dequant_slices(const void* const* records_dev, uint32_t n_slices
  * peers_dev is a HOST array of n_peers DEVICE pointers (copied at call time), 1 <= n_peers <= FCV2_MAX_PEERS.
  * sum_out_dev, if not NULL, receives the n fp32 sums (before the bf16 rounding).
  * fmt_in and fmt_out must agree in group and FCV2_F_SPIKE (bits, the metadata flags and the index width may differ; equal
- * bits take the fast kernel); other pairs give FCV2_ERR_UNSUPPORTED. */
+ * bits take a kernel specialised for the width, different bits one that switches on the input width at run time, a few
+ * percent slower); other pairs give FCV2_ERR_UNSUPPORTED. */
 int fcv2_reduce_requant(const void* const* peers_dev, int n_peers, uint64_t n, const fcv2_fmt_t* fmt_in,
                         const fcv2_fmt_t* fmt_out, void* packed_out_dev, float* sum_out_dev, void* hip_stream);
 
